@@ -1,0 +1,406 @@
+// Fused causal self-attention of one tensor-parallel shard (paper section 2.3: heads split over the
+// ranks; section 4.2: scale + implicit causal mask + softmax fused; here the two batched GEMMs
+// Q K^T and P V of the appendix are fused in as well, so the s x s matrix never reaches HBM).
+//
+// qkv is [s, b, 3*hp] with columns [Q heads | K heads | V heads]; for sample j and local head e the
+// row of token i starts at qkv + (i*b + j)*3*hp + {0, hp, 2hp} + e*dh.
+//
+// bf16 forward: S^T = K Q^T and O^T = V^T P^T on v_mfma_f32_32x32x16_bf16, so that the softmax
+// probabilities leave the first MFMA already in the register layout the second one wants as its
+// B operand.  One wave owns 32 queries; a block of 4 waves shares 64-key K and V^T tiles in LDS.
+// The "rowwise" kernels are the plain formulation (one wave per row): they are the fp32 path and the
+// reference-shaped fallback of the bf16 backward.
+#include "common.h"
+
+namespace ptdp {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+template <typename T> __device__ __forceinline__ float ld(const T* p);
+template <> __device__ __forceinline__ float ld<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ld<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <typename T> __device__ __forceinline__ void st(T* p, float v);
+template <> __device__ __forceinline__ void st<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// ------------------------------------------------------------------------------------------------
+// rowwise kernels: grid (s, heads, b), one wave per block; lane owns dims lane, lane+64, ... (dh <= 256)
+// ------------------------------------------------------------------------------------------------
+constexpr int kMaxDimsPerLane = 4;
+
+template <typename T>
+__global__ void __launch_bounds__(64)
+attn_fwd_rowwise(const T* __restrict__ qkv, T* __restrict__ ctx, float* __restrict__ lse, int s, int b, int heads,
+                 int dh) {
+  const int i = blockIdx.x, e = blockIdx.y, j = blockIdx.z, lane = threadIdx.x;
+  const int hp = heads * dh;
+  const size_t rs = (size_t)b * 3 * hp;  // token stride
+  const T* base = qkv + (size_t)j * 3 * hp + (size_t)e * dh;
+  const float scale = rsqrtf((float)dh);
+  float q[kMaxDimsPerLane], acc[kMaxDimsPerLane];
+#pragma unroll
+  for (int c = 0; c < kMaxDimsPerLane; ++c) {
+    const int d = lane + 64 * c;
+    q[c] = d < dh ? ld(base + (size_t)i * rs + d) : 0.f;
+    acc[c] = 0.f;
+  }
+  float m = -INFINITY, l = 0.f;
+  for (int kk = 0; kk <= i; ++kk) {
+    const T* kr = base + (size_t)kk * rs + hp;
+    const T* vr = kr + hp;
+    float dot = 0.f;
+#pragma unroll
+    for (int c = 0; c < kMaxDimsPerLane; ++c) {
+      const int d = lane + 64 * c;
+      if (d < dh) dot += q[c] * ld(kr + d);
+    }
+    const float sc = wave_sum(dot) * scale;
+    const float mn = fmaxf(m, sc);
+    const float corr = __expf(m - mn), p = __expf(sc - mn);
+    l = l * corr + p;
+#pragma unroll
+    for (int c = 0; c < kMaxDimsPerLane; ++c) {
+      const int d = lane + 64 * c;
+      if (d < dh) acc[c] = acc[c] * corr + p * ld(vr + d);
+    }
+    m = mn;
+  }
+#pragma unroll
+  for (int c = 0; c < kMaxDimsPerLane; ++c) {
+    const int d = lane + 64 * c;
+    if (d < dh) st(ctx + ((size_t)i * b + j) * hp + (size_t)e * dh + d, acc[c] / l);
+  }
+  if (lane == 0) lse[((size_t)j * heads + e) * s + i] = m + __logf(l);
+}
+
+// delta[j][e][i] = sum_d dctx * ctx
+template <typename T>
+__global__ void __launch_bounds__(64)
+attn_delta_rowwise(const T* __restrict__ ctx, const T* __restrict__ dctx, float* __restrict__ delta, int s, int b,
+                   int heads, int dh) {
+  const int i = blockIdx.x, e = blockIdx.y, j = blockIdx.z, lane = threadIdx.x;
+  const size_t off = ((size_t)i * b + j) * heads * dh + (size_t)e * dh;
+  float a = 0.f;
+  for (int d = lane; d < dh; d += 64) a += ld(ctx + off + d) * ld(dctx + off + d);
+  a = wave_sum(a);
+  if (lane == 0) delta[((size_t)j * heads + e) * s + i] = a;
+}
+
+// dQ of query row i: sum over keys kk <= i of dS[i][kk] K[kk] / sqrt(dh)
+template <typename T>
+__global__ void __launch_bounds__(64)
+attn_bwd_dq_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, const float* __restrict__ lse,
+                    const float* __restrict__ delta, T* __restrict__ dqkv, int s, int b, int heads, int dh) {
+  const int i = blockIdx.x, e = blockIdx.y, j = blockIdx.z, lane = threadIdx.x;
+  const int hp = heads * dh;
+  const size_t rs = (size_t)b * 3 * hp;
+  const T* base = qkv + (size_t)j * 3 * hp + (size_t)e * dh;
+  const float scale = rsqrtf((float)dh);
+  const float L = lse[((size_t)j * heads + e) * s + i], D = delta[((size_t)j * heads + e) * s + i];
+  float q[kMaxDimsPerLane], dc[kMaxDimsPerLane], acc[kMaxDimsPerLane];
+#pragma unroll
+  for (int c = 0; c < kMaxDimsPerLane; ++c) {
+    const int d = lane + 64 * c;
+    q[c] = d < dh ? ld(base + (size_t)i * rs + d) : 0.f;
+    dc[c] = d < dh ? ld(dctx + ((size_t)i * b + j) * hp + (size_t)e * dh + d) : 0.f;
+    acc[c] = 0.f;
+  }
+  for (int kk = 0; kk <= i; ++kk) {
+    const T* kr = base + (size_t)kk * rs + hp;
+    const T* vr = kr + hp;
+    float dot = 0.f, dpv = 0.f;
+    float kv[kMaxDimsPerLane];
+#pragma unroll
+    for (int c = 0; c < kMaxDimsPerLane; ++c) {
+      const int d = lane + 64 * c;
+      kv[c] = d < dh ? ld(kr + d) : 0.f;
+      dot += q[c] * kv[c];
+      if (d < dh) dpv += dc[c] * ld(vr + d);
+    }
+    const float p = __expf(wave_sum(dot) * scale - L);
+    const float ds = p * (wave_sum(dpv) - D) * scale;
+#pragma unroll
+    for (int c = 0; c < kMaxDimsPerLane; ++c) acc[c] += ds * kv[c];
+  }
+#pragma unroll
+  for (int c = 0; c < kMaxDimsPerLane; ++c) {
+    const int d = lane + 64 * c;
+    if (d < dh) st(dqkv + (size_t)i * rs + (size_t)j * 3 * hp + (size_t)e * dh + d, acc[c]);
+  }
+}
+
+// dK, dV of key row kk: sums over queries i >= kk
+template <typename T>
+__global__ void __launch_bounds__(64)
+attn_bwd_dkv_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, const float* __restrict__ lse,
+                     const float* __restrict__ delta, T* __restrict__ dqkv, int s, int b, int heads, int dh) {
+  const int kk = blockIdx.x, e = blockIdx.y, j = blockIdx.z, lane = threadIdx.x;
+  const int hp = heads * dh;
+  const size_t rs = (size_t)b * 3 * hp;
+  const T* base = qkv + (size_t)j * 3 * hp + (size_t)e * dh;
+  const float scale = rsqrtf((float)dh);
+  float kv[kMaxDimsPerLane], vv[kMaxDimsPerLane], dk[kMaxDimsPerLane], dv[kMaxDimsPerLane];
+#pragma unroll
+  for (int c = 0; c < kMaxDimsPerLane; ++c) {
+    const int d = lane + 64 * c;
+    kv[c] = d < dh ? ld(base + (size_t)kk * rs + hp + d) : 0.f;
+    vv[c] = d < dh ? ld(base + (size_t)kk * rs + 2 * hp + d) : 0.f;
+    dk[c] = dv[c] = 0.f;
+  }
+  for (int i = kk; i < s; ++i) {
+    const T* qr = base + (size_t)i * rs;
+    const T* dr = dctx + ((size_t)i * b + j) * hp + (size_t)e * dh;
+    float qv[kMaxDimsPerLane], dc[kMaxDimsPerLane];
+    float dot = 0.f, dpv = 0.f;
+#pragma unroll
+    for (int c = 0; c < kMaxDimsPerLane; ++c) {
+      const int d = lane + 64 * c;
+      qv[c] = d < dh ? ld(qr + d) : 0.f;
+      dc[c] = d < dh ? ld(dr + d) : 0.f;
+      dot += qv[c] * kv[c];
+      dpv += dc[c] * vv[c];
+    }
+    const size_t st_i = ((size_t)j * heads + e) * s + i;
+    const float p = __expf(wave_sum(dot) * scale - lse[st_i]);
+    const float ds = p * (wave_sum(dpv) - delta[st_i]) * scale;
+#pragma unroll
+    for (int c = 0; c < kMaxDimsPerLane; ++c) {
+      dv[c] += p * dc[c];
+      dk[c] += ds * qv[c];
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < kMaxDimsPerLane; ++c) {
+    const int d = lane + 64 * c;
+    if (d < dh) {
+      st(dqkv + (size_t)kk * rs + (size_t)j * 3 * hp + hp + (size_t)e * dh + d, dk[c]);
+      st(dqkv + (size_t)kk * rs + (size_t)j * 3 * hp + 2 * hp + (size_t)e * dh + d, dv[c]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// bf16 MFMA forward
+// ------------------------------------------------------------------------------------------------
+constexpr int kBQ = 128;   // queries per block (4 waves x 32)
+constexpr int kBKV = 64;   // keys per LDS tile
+constexpr int kVtStride = kBKV * 2 + 16;   // bytes per V^T row (64 keys) + pad
+
+// 8x8 transpose of 16-bit values: in[j] = 8 values of source row j; out[r] = element r of rows 0..7.
+__device__ __forceinline__ void transpose8x8_b16(const uint4 (&in)[8], uint4 (&out)[8]) {
+  const uint32_t* w = reinterpret_cast<const uint32_t*>(&in[0]);
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    uint32_t o[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const uint32_t x = w[(2 * d) * 4 + (r >> 1)], y = w[(2 * d + 1) * 4 + (r >> 1)];
+      o[d] = (r & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+    }
+    out[r] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+template <int DH>
+__global__ void __launch_bounds__(256)
+attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* __restrict__ lse, int s, int b,
+              int heads) {
+  constexpr int KSTRIDE = DH * 2 + 16;  // bytes per K row in LDS
+  constexpr int NKK = DH / 16;          // k16 steps over dh
+  constexpr int NDT = DH / 32;          // 32-row tiles of O^T
+  __shared__ __attribute__((aligned(16))) char k_lds[kBKV * KSTRIDE];
+  __shared__ __attribute__((aligned(16))) char vt_lds[DH * kVtStride];
+
+  const int qblk = gridDim.x - 1 - blockIdx.x;  // long rows first
+  const int e = blockIdx.y, j = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
+  const int hp = heads * DH;
+  const size_t rs = (size_t)b * 3 * hp;
+  const bf16_t* base = qkv + (size_t)j * 3 * hp + (size_t)e * DH;
+  const int q_first = qblk * kBQ + wave * 32;  // first query of this wave
+  const int my_q = q_first + l31;
+  const float c2 = rsqrtf((float)DH) * 1.4426950408889634f;  // scale * log2(e)
+
+  // Q^T fragments (B operand): lane = query, 8 consecutive dh per k16 step
+  bf16x8_t qf[NKK];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) {
+    uint4 t = make_uint4(0, 0, 0, 0);
+    if (my_q < s) t = *reinterpret_cast<const uint4*>(base + (size_t)my_q * rs + kk * 16 + half * 8);
+    qf[kk] = *reinterpret_cast<bf16x8_t*>(&t);
+  }
+
+  f32x16_t o[NDT];
+#pragma unroll
+  for (int d = 0; d < NDT; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int q_last_blk = min(s, (qblk + 1) * kBQ) - 1;
+  const int ntiles = q_last_blk / kBKV + 1;
+  for (int kt = 0; kt < ntiles; ++kt) {
+    const int key0 = kt * kBKV;
+    __syncthreads();
+    // K tile, direct: 64 keys x DH/8 chunks
+    for (int v = threadIdx.x; v < kBKV * (DH / 8); v += 256) {
+      const int key = v / (DH / 8), ch = v % (DH / 8);
+      uint4 t = make_uint4(0, 0, 0, 0);
+      if (key0 + key < s) t = *reinterpret_cast<const uint4*>(base + (size_t)(key0 + key) * rs + hp + ch * 8);
+      *reinterpret_cast<uint4*>(k_lds + key * KSTRIDE + ch * 16) = t;
+    }
+    // V tile, transposed into [dh][key]: 8x8 blocks, 8 key groups x DH/8 dh groups
+    for (int blk = threadIdx.x; blk < 8 * (DH / 8); blk += 256) {
+      const int kg = blk & 7, dg = blk >> 3;
+      uint4 in[8], out[8];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int key = key0 + kg * 8 + r;
+        in[r] = key < s ? *reinterpret_cast<const uint4*>(base + (size_t)key * rs + 2 * hp + dg * 8)
+                        : make_uint4(0, 0, 0, 0);
+      }
+      transpose8x8_b16(in, out);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) *reinterpret_cast<uint4*>(vt_lds + (dg * 8 + r) * kVtStride + kg * 16) = out[r];
+    }
+    __syncthreads();
+    if (key0 > q_first + 31) continue;  // every key of the tile is in this wave's future
+
+    // S^T[key][query] for the two 32-key halves of the tile
+    f32x16_t sacc[2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) {
+        const bf16x8_t kf =
+            *reinterpret_cast<const bf16x8_t*>(k_lds + (sub * 32 + l31) * KSTRIDE + (kk * 2 + half) * 16);
+        sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[sub], 0, 0, 0);
+      }
+    }
+    // causal mask (also hides keys >= s, which are > every valid query) and running max
+    const bool need_mask = key0 + kBKV - 1 > q_first;
+    float mx = m_run;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (need_mask && key > my_q) sacc[sub][r] = -INFINITY;
+        mx = fmaxf(mx, sacc[sub][r]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float corr = exp2f((m_run - mx) * c2);
+    m_run = mx;
+    l_run *= corr;
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] *= corr;
+    // P^T as B operand: registers 8*ks .. 8*ks+7 of each half tile serve k16 step ks
+    bf16x8_t pf[2][2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        uint32_t w[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const float p0 = exp2f((sacc[sub][ks * 8 + 2 * d] - mx) * c2);
+          const float p1 = exp2f((sacc[sub][ks * 8 + 2 * d + 1] - mx) * c2);
+          l_run += p0 + p1;
+          w[d] = pack_bf16x2(p0, p1);
+        }
+        uint4 t = make_uint4(w[0], w[1], w[2], w[3]);
+        pf[sub][ks] = *reinterpret_cast<bf16x8_t*>(&t);
+      }
+    // O^T[dh][query] += V^T[dh][key] P^T[key][query]; the A operand takes its 8 keys in the same order
+    // as the accumulator rows above: keys 16*ks + 4*half + 0..3 and 16*ks + 8 + 4*half + 0..3.
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          const char* row = vt_lds + (d * 32 + l31) * kVtStride + (sub * 32 + ks * 16 + 4 * half) * 2;
+          uint2 lo = *reinterpret_cast<const uint2*>(row);
+          uint2 hi = *reinterpret_cast<const uint2*>(row + 16);
+          uint4 t = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8_t*>(&t), pf[sub][ks], o[d], 0, 0, 0);
+        }
+  }
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (my_q < s) {
+    const float inv = 1.f / l_run;
+    bf16_t* out = ctx + ((size_t)my_q * b + j) * hp + (size_t)e * DH;
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 w;
+        w.x = pack_bf16x2(o[d][4 * g] * inv, o[d][4 * g + 1] * inv);
+        w.y = pack_bf16x2(o[d][4 * g + 2] * inv, o[d][4 * g + 3] * inv);
+        *reinterpret_cast<uint2*>(out + d * 32 + 8 * g + 4 * half) = w;
+      }
+    if (half == 0) lse[((size_t)j * heads + e) * s + my_q] = m_run * rsqrtf((float)DH) + __logf(l_run);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host launchers
+// ------------------------------------------------------------------------------------------------
+bool attn_dh_supported(int dtype, int dh) {
+  if (dh <= 0 || dh % 8 != 0) return false;
+  if (dtype == PTDP_F32) return dh <= 64 * kMaxDimsPerLane;
+  return dh == 64 || dh == 128 || dh == 160;
+}
+
+static inline double attn_flops(int s, int b, int heads, int dh) { return 4.0 * b * heads * (double)s * s * dh; }
+
+int launch_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, int b, int heads, int dh,
+                    hipStream_t stream) {
+  if (s == 0 || b == 0 || heads == 0) return PTDP_OK;
+  if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
+  Launch L(PTDP_K_ATTN_FWD, attn_flops(s, b, heads, dh), stream);
+  if (dtype == PTDP_F32) {
+    hipLaunchKernelGGL((attn_fwd_rowwise<float>), dim3(s, heads, b), dim3(64), 0, stream, (const float*)qkv,
+                       (float*)ctx, lse, s, b, heads, dh);
+  } else {
+    const dim3 grid((s + kBQ - 1) / kBQ, heads, b);
+    const bf16_t* q = (const bf16_t*)qkv;
+    bf16_t* c = (bf16_t*)ctx;
+    if (dh == 64) hipLaunchKernelGGL((attn_fwd_mfma<64>), grid, dim3(256), 0, stream, q, c, lse, s, b, heads);
+    else if (dh == 128) hipLaunchKernelGGL((attn_fwd_mfma<128>), grid, dim3(256), 0, stream, q, c, lse, s, b, heads);
+    else hipLaunchKernelGGL((attn_fwd_mfma<160>), grid, dim3(256), 0, stream, q, c, lse, s, b, heads);
+  }
+  return L.status();
+}
+
+template <typename T>
+static int attn_bwd_rowwise_t(const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
+                              float* delta, int s, int b, int heads, int dh, hipStream_t stream) {
+  const dim3 grid(s, heads, b);
+  hipLaunchKernelGGL((attn_delta_rowwise<T>), grid, dim3(64), 0, stream, (const T*)ctx, (const T*)dctx, delta, s, b,
+                     heads, dh);
+  hipLaunchKernelGGL((attn_bwd_dq_rowwise<T>), grid, dim3(64), 0, stream, (const T*)qkv, (const T*)dctx, lse, delta,
+                     (T*)dqkv, s, b, heads, dh);
+  hipLaunchKernelGGL((attn_bwd_dkv_rowwise<T>), grid, dim3(64), 0, stream, (const T*)qkv, (const T*)dctx, lse, delta,
+                     (T*)dqkv, s, b, heads, dh);
+  return PTDP_OK;
+}
+
+int launch_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
+                    float* delta, int s, int b, int heads, int dh, hipStream_t stream) {
+  if (s == 0 || b == 0 || heads == 0) return PTDP_OK;
+  if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
+  Launch L(PTDP_K_ATTN_BWD, 2.0 * attn_flops(s, b, heads, dh), stream);
+  if (dtype == PTDP_F32)
+    attn_bwd_rowwise_t<float>(qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, stream);
+  else
+    attn_bwd_rowwise_t<bf16_t>(qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, stream);
+  return L.status();
+}
+
+}  // namespace ptdp

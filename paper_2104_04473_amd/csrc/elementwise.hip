@@ -1,0 +1,573 @@
+// Bandwidth-bound kernels of the layer: LayerNorm, bias+GeLU, bias+dropout+add (paper section 4.2
+// names the two fusions; LayerNorm is implied by the 13h term of eq. (2)) and their backward passes.
+// All of them move 16 bytes per lane per access, keep fp32 arithmetic, and reduce with wavefront
+// shuffles; column sums (bias / LayerNorm parameter gradients) are two-stage and deterministic.
+#include "common.h"
+
+namespace ptdp {
+
+static constexpr int kColRows = 32;  // rows per block in the column-sum producers
+
+// ------------------------------------------------------------------------------------------------
+// LayerNorm forward: one block per row, the row lives in registers (VPT 16-byte vectors per thread).
+// ------------------------------------------------------------------------------------------------
+template <typename T, int VPT>
+__global__ void layernorm_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gain, const T* __restrict__ bias,
+                                     T* __restrict__ u, float* __restrict__ mu, float* __restrict__ rstd,
+                                     T* __restrict__ x_copy, int width, float eps) {
+  constexpr int N = Vec16<T>::N;
+  __shared__ float red[16];
+  const int nvec = width / N;
+  const size_t row = blockIdx.x;
+  const T* xr = x + row * width;
+  float v[VPT][N];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int c = threadIdx.x + i * blockDim.x;
+    if (c < nvec) {
+      Vec16<T> t;
+      t.load(xr + (size_t)c * N);
+      if (x_copy) t.store(x_copy + row * width + (size_t)c * N);
+      t.unpack(v[i]);
+#pragma unroll
+      for (int j = 0; j < N; ++j) sum += v[i][j];
+    }
+  }
+  const float mean = block_sum(sum, red) / (float)width;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int c = threadIdx.x + i * blockDim.x;
+    if (c < nvec) {
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        const float d = v[i][j] - mean;
+        sq += d * d;
+      }
+    }
+  }
+  const float r = rsqrtf(block_sum(sq, red) / (float)width + eps);
+  if (threadIdx.x == 0) {
+    mu[row] = mean;
+    rstd[row] = r;
+  }
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int c = threadIdx.x + i * blockDim.x;
+    if (c < nvec) {
+      Vec16<T> g, b, o;
+      float gf[N], bf[N], of[N];
+      g.load(gain + (size_t)c * N);
+      b.load(bias + (size_t)c * N);
+      g.unpack(gf);
+      b.unpack(bf);
+#pragma unroll
+      for (int j = 0; j < N; ++j) of[j] = gf[j] * ((v[i][j] - mean) * r) + bf[j];
+      o.pack(of);
+      o.store(u + row * width + (size_t)c * N);
+    }
+  }
+}
+
+// LayerNorm backward.  Block handles `rpb` consecutive rows; per row
+//   xhat = (x-mu)*rstd, dxhat = du*gain, dx = resid + rstd*(dxhat - mean(dxhat) - xhat*mean(dxhat*xhat)).
+// Per-thread column partials of sum(du*xhat) and sum(du) go to part[blockIdx][2*width].
+template <typename T, int VPT>
+__global__ void layernorm_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const T* __restrict__ gain,
+                                     const float* __restrict__ mu, const float* __restrict__ rstd,
+                                     const T* resid, T* dx, float* __restrict__ part, int rows, int width,
+                                     int rpb) {
+  constexpr int N = Vec16<T>::N;
+  __shared__ float red[16];
+  const int nvec = width / N;
+  float gf[VPT][N], acc_g[VPT][N], acc_b[VPT][N];
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int c = threadIdx.x + i * blockDim.x;
+#pragma unroll
+    for (int j = 0; j < N; ++j) acc_g[i][j] = acc_b[i][j] = 0.f;
+    if (c < nvec) {
+      Vec16<T> g;
+      g.load(gain + (size_t)c * N);
+      g.unpack(gf[i]);
+    }
+  }
+  const int r0 = blockIdx.x * rpb;
+  const int r1 = min(rows, r0 + rpb);
+  for (int row = r0; row < r1; ++row) {
+    const size_t base = (size_t)row * width;
+    const float m = mu[row], rs = rstd[row];
+    float dv[VPT][N], xh[VPT][N];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int c = threadIdx.x + i * blockDim.x;
+      if (c < nvec) {
+        Vec16<T> a, b;
+        a.load(du + base + (size_t)c * N);
+        b.load(x + base + (size_t)c * N);
+        a.unpack(dv[i]);
+        b.unpack(xh[i]);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+          xh[i][j] = (xh[i][j] - m) * rs;
+          acc_g[i][j] += dv[i][j] * xh[i][j];
+          acc_b[i][j] += dv[i][j];
+          const float dxh = dv[i][j] * gf[i][j];
+          s1 += dxh;
+          s2 += dxh * xh[i][j];
+        }
+      }
+    }
+    const float c1 = block_sum(s1, red) / (float)width;
+    const float c2 = block_sum(s2, red) / (float)width;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int c = threadIdx.x + i * blockDim.x;
+      if (c < nvec) {
+        float of[N];
+        if (resid) {
+          Vec16<T> rr;
+          rr.load(resid + base + (size_t)c * N);
+          rr.unpack(of);
+        } else {
+#pragma unroll
+          for (int j = 0; j < N; ++j) of[j] = 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) of[j] += rs * (dv[i][j] * gf[i][j] - c1 - xh[i][j] * c2);
+        Vec16<T> o;
+        o.pack(of);
+        o.store(dx + base + (size_t)c * N);
+      }
+    }
+  }
+  float* prow = part + (size_t)blockIdx.x * 2 * width;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int c = threadIdx.x + i * blockDim.x;
+    if (c < nvec) {
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        prow[(size_t)c * N + j] = acc_g[i][j];
+        prow[(size_t)width + (size_t)c * N + j] = acc_b[i][j];
+      }
+    }
+  }
+}
+
+// out[c] += sum over parts of part[p][c]  (second stage of every column sum; fixed order).
+__global__ void colsum_finish_kernel(const float* __restrict__ part, int nparts, int stride, float* out0,
+                                     float* out1, int width) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= width) return;
+  float a = 0.f, b = 0.f;
+  for (int p = 0; p < nparts; ++p) {
+    a += part[(size_t)p * stride + c];
+    if (out1) b += part[(size_t)p * stride + width + c];
+  }
+  out0[c] += a;
+  if (out1) out1[c] += b;
+}
+
+// ------------------------------------------------------------------------------------------------
+// bias + GeLU
+// ------------------------------------------------------------------------------------------------
+template <int MODE> __device__ __forceinline__ float gelu_f(float z) {
+  if (MODE == PTDP_GELU_TANH) {
+    const float c = 0.7978845608028654f;
+    return 0.5f * z * (1.f + tanhf(c * (z + 0.044715f * z * z * z)));
+  }
+  return 0.5f * z * (1.f + erff(z * 0.7071067811865476f));
+}
+template <int MODE> __device__ __forceinline__ float gelu_grad_f(float z) {
+  if (MODE == PTDP_GELU_TANH) {
+    const float c = 0.7978845608028654f;
+    const float th = tanhf(c * (z + 0.044715f * z * z * z));
+    return 0.5f * (1.f + th) + 0.5f * z * (1.f - th * th) * c * (1.f + 3.f * 0.044715f * z * z);
+  }
+  return 0.5f * (1.f + erff(z * 0.7071067811865476f)) + z * __expf(-0.5f * z * z) * 0.3989422804014327f;
+}
+
+template <typename T, int MODE>
+__global__ void bias_gelu_fwd_kernel(const T* __restrict__ z, const T* __restrict__ bias, T* __restrict__ g,
+                                     size_t total_vec, int nvec_row) {
+  constexpr int N = Vec16<T>::N;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total_vec; i += (size_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % nvec_row);
+    Vec16<T> a, b;
+    float af[N], bf[N];
+    a.load(z + i * N);
+    b.load(bias + (size_t)c * N);
+    a.unpack(af);
+    b.unpack(bf);
+#pragma unroll
+    for (int j = 0; j < N; ++j) af[j] = gelu_f<MODE>(af[j] + bf[j]);
+    a.pack(af);
+    a.store(g + i * N);
+  }
+}
+
+// grid (column slabs, row tiles of kColRows); thread owns one 16-byte column group.
+template <typename T, int MODE>
+__global__ void bias_gelu_bwd_kernel(const T* dg, const T* __restrict__ z, const T* __restrict__ bias, T* dz,
+                                     float* __restrict__ part, int rows, int width) {
+  constexpr int N = Vec16<T>::N;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= width / N) return;
+  float bf[N], acc[N];
+  Vec16<T> b;
+  b.load(bias + (size_t)c * N);
+  b.unpack(bf);
+#pragma unroll
+  for (int j = 0; j < N; ++j) acc[j] = 0.f;
+  const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
+  for (int r = r0; r < r1; ++r) {
+    const size_t off = (size_t)r * width + (size_t)c * N;
+    Vec16<T> a, zz;
+    float af[N], zf[N];
+    a.load(dg + off);
+    zz.load(z + off);
+    a.unpack(af);
+    zz.unpack(zf);
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      af[j] *= gelu_grad_f<MODE>(zf[j] + bf[j]);
+      acc[j] += af[j];
+    }
+    a.pack(af);
+    a.store(dz + off);
+  }
+#pragma unroll
+  for (int j = 0; j < N; ++j) part[(size_t)blockIdx.y * width + (size_t)c * N + j] = acc[j];
+}
+
+// ------------------------------------------------------------------------------------------------
+// bias + dropout + add
+// ------------------------------------------------------------------------------------------------
+// keep flags of the N elements starting at flat index idx (idx % N == 0, N in {4, 8}).
+template <int N> __device__ __forceinline__ void keep_flags(uint64_t key, uint64_t idx, uint32_t thr, bool* keep) {
+#pragma unroll
+  for (int w = 0; w < N / 4; ++w) {
+    const uint64_t r = mix64(key + kGolden * ((idx >> 2) + w));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) keep[4 * w + j] = (uint32_t)((r >> (16 * j)) & 0xffffu) >= thr;
+  }
+}
+
+template <typename T>
+__global__ void bda_fwd_kernel(const T* __restrict__ in, const T* __restrict__ bias, const T* __restrict__ resid,
+                               T* __restrict__ out, size_t total_vec, int nvec_row, uint64_t key, uint32_t thr,
+                               float scale) {
+  constexpr int N = Vec16<T>::N;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total_vec; i += (size_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % nvec_row);
+    Vec16<T> a, b, r;
+    float af[N], bf[N], rf[N];
+    bool keep[N];
+    a.load(in + i * N);
+    r.load(resid + i * N);
+    b.load(bias + (size_t)c * N);
+    a.unpack(af);
+    b.unpack(bf);
+    r.unpack(rf);
+    keep_flags<N>(key, (uint64_t)i * N, thr, keep);
+#pragma unroll
+    for (int j = 0; j < N; ++j) rf[j] += keep[j] ? (af[j] + bf[j]) * scale : 0.f;
+    r.pack(rf);
+    r.store(out + i * N);
+  }
+}
+
+template <typename T>
+__global__ void bda_bwd_kernel(const T* __restrict__ dout, T* __restrict__ din, float* __restrict__ part, int rows,
+                               int width, uint64_t key, uint32_t thr, float scale) {
+  constexpr int N = Vec16<T>::N;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= width / N) return;
+  float acc[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) acc[j] = 0.f;
+  const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
+  for (int r = r0; r < r1; ++r) {
+    const size_t off = (size_t)r * width + (size_t)c * N;
+    Vec16<T> a;
+    float af[N];
+    bool keep[N];
+    a.load(dout + off);
+    a.unpack(af);
+    keep_flags<N>(key, (uint64_t)off, thr, keep);
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      af[j] = keep[j] ? af[j] * scale : 0.f;
+      acc[j] += af[j];
+    }
+    a.pack(af);
+    a.store(din + off);
+  }
+#pragma unroll
+  for (int j = 0; j < N; ++j) part[(size_t)blockIdx.y * width + (size_t)c * N + j] = acc[j];
+}
+
+// part[blockIdx.y][c] = sum of in[r][c] over the block's kColRows rows (first stage of a bias gradient
+// whose producer lives in another kernel, e.g. the QKV bias).
+template <typename T>
+__global__ void colsum_rows_kernel(const T* __restrict__ in, float* __restrict__ part, int rows, int width) {
+  constexpr int N = Vec16<T>::N;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= width / N) return;
+  float acc[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) acc[j] = 0.f;
+  const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
+  for (int r = r0; r < r1; ++r) {
+    Vec16<T> a;
+    float af[N];
+    a.load(in + (size_t)r * width + (size_t)c * N);
+    a.unpack(af);
+#pragma unroll
+    for (int j = 0; j < N; ++j) acc[j] += af[j];
+  }
+#pragma unroll
+  for (int j = 0; j < N; ++j) part[(size_t)blockIdx.y * width + (size_t)c * N + j] = acc[j];
+}
+
+__global__ void dropout_mask_kernel(uint8_t* keep, int64_t n, uint64_t key, uint32_t thr) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const uint64_t r = mix64(key + kGolden * ((uint64_t)i >> 2));
+    keep[i] = ((uint32_t)((r >> (16 * (i & 3))) & 0xffffu) >= thr) ? 1 : 0;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host launchers
+// ------------------------------------------------------------------------------------------------
+static inline int ln_threads(int nvec, int* vpt) {
+  // smallest register cache that covers the row with at most 512 threads
+  int threads = 64;
+  while (threads < 512 && threads < nvec) threads <<= 1;
+  int v = (nvec + threads - 1) / threads;
+  int p = 1;
+  while (p < v) p <<= 1;
+  *vpt = p;
+  return threads;
+}
+
+static inline int ln_rows_per_block(int rows) {
+  int rpb = (rows + 255) / 256;
+  if (rpb < 1) rpb = 1;
+  if (rpb > 16) rpb = 16;
+  return rpb;
+}
+
+size_t colsum_scratch_bytes(int rows, int width) {
+  // enough for either producer: LayerNorm backward writes ceil(rows / rpb) parts (its `width` is twice
+  // the row width), the row-tile producers write ceil(rows / kColRows) parts.
+  if (rows <= 0 || width <= 0) return 0;
+  const int rpb = ln_rows_per_block(rows);
+  size_t parts = (size_t)((rows + rpb - 1) / rpb);
+  const size_t tiles = (size_t)((rows + kColRows - 1) / kColRows);
+  if (tiles > parts) parts = tiles;
+  return parts * (size_t)width * sizeof(float);
+}
+
+template <typename T>
+static int ln_fwd_t(const void* x, const void* gain, const void* bias, void* u, float* mu, float* rstd, void* x_copy,
+                    int rows, int width, float eps, hipStream_t st) {
+  constexpr int N = Vec16<T>::N;
+  int vpt;
+  const int threads = ln_threads(width / N, &vpt);
+  if (vpt > 8) return PTDP_E_UNSUPPORTED;
+  const double bytes = (double)rows * width * sizeof(T) * (x_copy ? 3 : 2);
+  Launch L(PTDP_K_LN_FWD, bytes, st);
+#define PTDP_LN_FWD(V)                                                                                        \
+  hipLaunchKernelGGL((layernorm_fwd_kernel<T, V>), dim3(rows), dim3(threads), 0, st, (const T*)x, (const T*)gain, \
+                     (const T*)bias, (T*)u, mu, rstd, (T*)x_copy, width, eps)
+  switch (vpt) {
+    case 1: PTDP_LN_FWD(1); break;
+    case 2: PTDP_LN_FWD(2); break;
+    case 4: PTDP_LN_FWD(4); break;
+    default: PTDP_LN_FWD(8); break;
+  }
+#undef PTDP_LN_FWD
+  return L.status();
+}
+
+int launch_layernorm_fwd(int dtype, const void* x, const void* gain, const void* bias, void* u, float* mu,
+                         float* rstd, void* x_copy, int rows, int width, float eps, hipStream_t st) {
+  if (rows == 0) return PTDP_OK;
+  return dtype == PTDP_BF16 ? ln_fwd_t<bf16_t>(x, gain, bias, u, mu, rstd, x_copy, rows, width, eps, st)
+                            : ln_fwd_t<float>(x, gain, bias, u, mu, rstd, x_copy, rows, width, eps, st);
+}
+
+static int colsum_finish(const float* part, int nparts, int stride, float* out0, float* out1, int width,
+                         hipStream_t st) {
+  Launch L(PTDP_K_COLSUM, (double)nparts * stride * sizeof(float), st);
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((width + 255) / 256), dim3(256), 0, st, part, nparts, stride, out0,
+                     out1, width);
+  return L.status();
+}
+
+template <typename T>
+static int ln_bwd_t(const void* du, const void* x, const void* gain, const float* mu, const float* rstd,
+                    const void* resid, void* dx, float* dgain, float* dbias, void* scratch, int rows, int width,
+                    hipStream_t st) {
+  constexpr int N = Vec16<T>::N;
+  int vpt;
+  const int threads = ln_threads(width / N, &vpt);
+  if (vpt > 8) return PTDP_E_UNSUPPORTED;
+  const int rpb = ln_rows_per_block(rows);
+  const int nblk = (rows + rpb - 1) / rpb;
+  float* part = (float*)scratch;
+  {
+    const double bytes = (double)rows * width * sizeof(T) * (resid ? 4 : 3);
+    Launch L(PTDP_K_LN_BWD, bytes, st);
+#define PTDP_LN_BWD(V)                                                                                          \
+  hipLaunchKernelGGL((layernorm_bwd_kernel<T, V>), dim3(nblk), dim3(threads), 0, st, (const T*)du, (const T*)x,  \
+                     (const T*)gain, mu, rstd, (const T*)resid, (T*)dx, part, rows, width, rpb)
+    switch (vpt) {
+      case 1: PTDP_LN_BWD(1); break;
+      case 2: PTDP_LN_BWD(2); break;
+      case 4: PTDP_LN_BWD(4); break;
+      default: PTDP_LN_BWD(8); break;
+    }
+#undef PTDP_LN_BWD
+    if (L.status() != PTDP_OK) return L.status();
+  }
+  return colsum_finish(part, nblk, 2 * width, dgain, dbias, width, st);
+}
+
+int launch_layernorm_bwd(int dtype, const void* du, const void* x, const void* gain, const float* mu,
+                         const float* rstd, const void* resid, void* dx, float* dgain, float* dbias,
+                         void* scratch, int rows, int width, hipStream_t st) {
+  if (rows == 0) return PTDP_OK;
+  return dtype == PTDP_BF16
+             ? ln_bwd_t<bf16_t>(du, x, gain, mu, rstd, resid, dx, dgain, dbias, scratch, rows, width, st)
+             : ln_bwd_t<float>(du, x, gain, mu, rstd, resid, dx, dgain, dbias, scratch, rows, width, st);
+}
+
+static inline int stream_grid(size_t total_vec) {
+  size_t blocks = (total_vec + 255) / 256;
+  const size_t cap = 256 * 16;  // 16 blocks per CU, grid-stride beyond
+  return (int)(blocks < cap ? (blocks ? blocks : 1) : cap);
+}
+
+template <typename T>
+static int gelu_fwd_t(int mode, const void* z, const void* bias, void* g, int rows, int width, hipStream_t st) {
+  constexpr int N = Vec16<T>::N;
+  const size_t total = (size_t)rows * width / N;
+  Launch L(PTDP_K_GELU_FWD, (double)rows * width * sizeof(T) * 2, st);
+  if (mode == PTDP_GELU_TANH)
+    hipLaunchKernelGGL((bias_gelu_fwd_kernel<T, PTDP_GELU_TANH>), dim3(stream_grid(total)), dim3(256), 0, st,
+                       (const T*)z, (const T*)bias, (T*)g, total, width / N);
+  else
+    hipLaunchKernelGGL((bias_gelu_fwd_kernel<T, PTDP_GELU_ERF>), dim3(stream_grid(total)), dim3(256), 0, st,
+                       (const T*)z, (const T*)bias, (T*)g, total, width / N);
+  return L.status();
+}
+
+int launch_bias_gelu_fwd(int dtype, int mode, const void* z, const void* bias, void* g, int rows, int width,
+                         hipStream_t st) {
+  if (rows == 0) return PTDP_OK;
+  return dtype == PTDP_BF16 ? gelu_fwd_t<bf16_t>(mode, z, bias, g, rows, width, st)
+                            : gelu_fwd_t<float>(mode, z, bias, g, rows, width, st);
+}
+
+template <typename T>
+static int gelu_bwd_t(int mode, const void* dg, const void* z, const void* bias, void* dz, float* dbias,
+                      void* scratch, int rows, int width, hipStream_t st) {
+  constexpr int N = Vec16<T>::N;
+  const int nvec = width / N;
+  const dim3 grid((nvec + 255) / 256, (rows + kColRows - 1) / kColRows);
+  float* part = (float*)scratch;
+  {
+    Launch L(PTDP_K_GELU_BWD, (double)rows * width * sizeof(T) * 3, st);
+    if (mode == PTDP_GELU_TANH)
+      hipLaunchKernelGGL((bias_gelu_bwd_kernel<T, PTDP_GELU_TANH>), grid, dim3(256), 0, st, (const T*)dg,
+                         (const T*)z, (const T*)bias, (T*)dz, part, rows, width);
+    else
+      hipLaunchKernelGGL((bias_gelu_bwd_kernel<T, PTDP_GELU_ERF>), grid, dim3(256), 0, st, (const T*)dg,
+                         (const T*)z, (const T*)bias, (T*)dz, part, rows, width);
+    if (L.status() != PTDP_OK) return L.status();
+  }
+  return colsum_finish(part, grid.y, width, dbias, nullptr, width, st);
+}
+
+int launch_bias_gelu_bwd(int dtype, int mode, const void* dg, const void* z, const void* bias, void* dz,
+                         float* dbias, void* scratch, int rows, int width, hipStream_t st) {
+  if (rows == 0) return PTDP_OK;
+  return dtype == PTDP_BF16 ? gelu_bwd_t<bf16_t>(mode, dg, z, bias, dz, dbias, scratch, rows, width, st)
+                            : gelu_bwd_t<float>(mode, dg, z, bias, dz, dbias, scratch, rows, width, st);
+}
+
+template <typename T>
+static int bda_fwd_t(const void* in, const void* bias, const void* resid, void* out, int rows, int width, float p,
+                     uint64_t key, hipStream_t st) {
+  constexpr int N = Vec16<T>::N;
+  const size_t total = (size_t)rows * width / N;
+  Launch L(PTDP_K_BDA_FWD, (double)rows * width * sizeof(T) * 3, st);
+  hipLaunchKernelGGL((bda_fwd_kernel<T>), dim3(stream_grid(total)), dim3(256), 0, st, (const T*)in, (const T*)bias,
+                     (const T*)resid, (T*)out, total, width / N, key, p > 0.f ? dropout_threshold(p) : 0u,
+                     1.0f / (1.0f - p));
+  return L.status();
+}
+
+int launch_bda_fwd(int dtype, const void* in, const void* bias, const void* resid, void* out, int rows, int width,
+                   float p, uint64_t key, hipStream_t st) {
+  if (rows == 0) return PTDP_OK;
+  return dtype == PTDP_BF16 ? bda_fwd_t<bf16_t>(in, bias, resid, out, rows, width, p, key, st)
+                            : bda_fwd_t<float>(in, bias, resid, out, rows, width, p, key, st);
+}
+
+template <typename T>
+static int bda_bwd_t(const void* dout, void* din, float* dbias, void* scratch, int rows, int width, float p,
+                     uint64_t key, hipStream_t st) {
+  constexpr int N = Vec16<T>::N;
+  const int nvec = width / N;
+  const dim3 grid((nvec + 255) / 256, (rows + kColRows - 1) / kColRows);
+  float* part = (float*)scratch;
+  {
+    Launch L(PTDP_K_BDA_BWD, (double)rows * width * sizeof(T) * 2, st);
+    hipLaunchKernelGGL((bda_bwd_kernel<T>), grid, dim3(256), 0, st, (const T*)dout, (T*)din, part, rows, width, key,
+                       p > 0.f ? dropout_threshold(p) : 0u, 1.0f / (1.0f - p));
+    if (L.status() != PTDP_OK) return L.status();
+  }
+  return colsum_finish(part, grid.y, width, dbias, nullptr, width, st);
+}
+
+int launch_bda_bwd(int dtype, const void* dout, void* din, float* dbias, void* scratch, int rows, int width, float p,
+                   uint64_t key, hipStream_t st) {
+  if (rows == 0) return PTDP_OK;
+  return dtype == PTDP_BF16 ? bda_bwd_t<bf16_t>(dout, din, dbias, scratch, rows, width, p, key, st)
+                            : bda_bwd_t<float>(dout, din, dbias, scratch, rows, width, p, key, st);
+}
+
+template <typename T>
+static int colsum_t(const void* in, float* out, void* scratch, int rows, int width, hipStream_t st) {
+  constexpr int N = Vec16<T>::N;
+  const dim3 grid((width / N + 255) / 256, (rows + kColRows - 1) / kColRows);
+  float* part = (float*)scratch;
+  {
+    Launch L(PTDP_K_COLSUM, (double)rows * width * sizeof(T), st);
+    hipLaunchKernelGGL((colsum_rows_kernel<T>), grid, dim3(256), 0, st, (const T*)in, part, rows, width);
+    if (L.status() != PTDP_OK) return L.status();
+  }
+  return colsum_finish(part, grid.y, width, out, nullptr, width, st);
+}
+
+int launch_colsum(int dtype, const void* in, float* out, void* scratch, int rows, int width, hipStream_t st) {
+  if (rows == 0) return PTDP_OK;
+  return dtype == PTDP_BF16 ? colsum_t<bf16_t>(in, out, scratch, rows, width, st)
+                            : colsum_t<float>(in, out, scratch, rows, width, st);
+}
+
+int launch_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t key, hipStream_t st) {
+  if (n == 0) return PTDP_OK;
+  Launch L(PTDP_K_OTHER, (double)n, st);
+  hipLaunchKernelGGL(dropout_mask_kernel, dim3(stream_grid((size_t)n)), dim3(256), 0, st, keep, n, key,
+                     p > 0.f ? dropout_threshold(p) : 0u);
+  return L.status();
+}
+
+}  // namespace ptdp

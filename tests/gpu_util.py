@@ -1,0 +1,84 @@
+"""Helpers of the GPU parity tests: torch is used for device memory only."""
+import ctypes as C
+
+import numpy as np
+import torch
+
+from oracle import gpt_layer as L
+from paper_2104_04473_amd import binding as B
+from paper_2104_04473_amd import synth
+
+TOL = {B.F32: 1e-4, B.BF16: 2e-2}      # relative L2 error per tensor (spec tolerances)
+
+
+def tdt(dtype):
+    return torch.bfloat16 if dtype == B.BF16 else torch.float32
+
+
+def np64(t):
+    """Exact fp64 copy of a device tensor (bf16 -> fp32 -> fp64 loses nothing)."""
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def rel_l2(got, want):
+    got = np.asarray(got, dtype=np.float64); want = np.asarray(want, dtype=np.float64)
+    den = np.linalg.norm(want.ravel())
+    num = np.linalg.norm((got - want).ravel())
+    return num / den if den > 0 else num
+
+
+def assert_close(got, want, dtype, what, factor=1.0):
+    err = rel_l2(got, want)
+    assert np.isfinite(np.asarray(got, dtype=np.float64)).all(), what + ": non-finite values"
+    assert err <= TOL[dtype] * factor, "%s: relative L2 error %.3e > %.1e" % (what, err, TOL[dtype] * factor)
+    return err
+
+
+def randn(shape, dtype, seed, scale=1.0, device="cuda"):
+    g = torch.Generator(device="cpu"); g.manual_seed(seed)
+    return (scale * torch.randn(shape, generator=g, dtype=torch.float32)).to(tdt(dtype)).to(device).contiguous()
+
+
+def dev_bytes(n):
+    return torch.empty(max(int(n), 16), dtype=torch.uint8, device="cuda")
+
+
+def stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+def oracle_cfg(cfg):
+    return L.LayerConfig(h=cfg.h, a=cfg.a, t=cfg.t, s=cfg.s, b=cfg.b, p_hidden=float(np.float32(cfg.p_hidden)),
+                         ln_eps=float(np.float32(cfg.ln_eps)), gelu_tanh=(cfg.gelu_mode == B.GELU_TANH), seed=cfg.seed)
+
+
+def params_np(params):
+    return {k: np64(v) for k, v in params.items()}
+
+
+class LayerRig:
+    """A chunk of n layers on the GPU with seeded parameters, zeroed grads, stash and workspace."""
+
+    def __init__(self, cfg, n_layers=1, first_layer=0, seed=100):
+        self.cfg = cfg
+        self.chunk = B.Chunk(cfg, n_layers, first_layer)
+        self.params = [synth.layer_params(cfg.h, cfg.a, cfg.t, cfg.dtype, seed + i, device="cpu") for i in range(n_layers)]
+        self.params = [{k: v.cuda() for k, v in P.items()} for P in self.params]
+        self.grads = [synth.zero_grads(cfg.h, cfg.a, cfg.t, "cuda") for _ in range(n_layers)]
+        for i in range(n_layers):
+            self.chunk.bind(i, self.params[i], self.grads[i])
+        self.stash = dev_bytes(self.chunk.stash_bytes())
+        self.ws = dev_bytes(self.chunk.workspace_bytes())
+        self.layer_stash_bytes = B.ptdp_layer_stash_bytes(C.byref(cfg))
+        self.offsets = B.stash_offsets(cfg)
+
+    def field(self, layer, name, shape, dtype=None):
+        """View of a stash field as a tensor."""
+        dt = tdt(self.cfg.dtype) if dtype is None else dtype
+        n = int(np.prod(shape)) * torch.empty((), dtype=dt).element_size()
+        off = layer * self.layer_stash_bytes + self.offsets[name]
+        return self.stash[off:off + n].view(dt).view(*shape)
