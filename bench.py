@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-GPU PTD-P compute path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c3|c2|c5] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path over one microbatch of synthetic input: forward of every
+layer of the stage shard, then backward of every layer (for c5: the whole interleaved 1F1B order of
+one device, 2 chunks x 8 microbatches).  Inputs, parameters, gradient accumulators, stash and
+workspace are resident in HBM before the timed region.  Prints ONE JSON line.
+
+value       model TFLOP/s = 3 x (24 b s h^2 + 4 b s^2 h)/t per layer and microbatch (paper appendix; no
+            recompute forward is executed, so the paper's factor 4 is not used) / wall time
+roofline    the GEMM family with the largest share of the step, timed live with HIP events on the
+            launch stream in a second pass over the same steps (event pairs around every launch)
+cpu_baseline the fp64 numpy oracle, one layer forward+backward at the workload's shape on a bounded
+            number of sequence positions, on the host cores of this machine
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+WORKLOADS = {
+    # name: (h, a, t, s, b, layers, description)
+    "c2": dict(h=2048, a=16, t=1, s=2048, b=4, layers=4, desc="4 GPT layers h=2048 a=16 s=2048 b=4 t=1"),
+    "c3": dict(h=12288, a=96, t=8, s=2048, b=1, layers=2, desc="GPT-3 175B-shaped shard, 2 layers, t=8"),
+    "c4": dict(h=25600, a=160, t=8, s=2048, b=1, layers=4, desc="1T-parameter-shaped stage shard, 4 layers, t=8"),
+    "c5": dict(h=12288, a=96, t=8, s=2048, b=1, layers=4, chunks=2, m=8, p=4, rank=0,
+               desc="interleaved 1F1B share of one device: 2 chunks x 4 layers, m=8, p=4, rank 0"),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-positions", type=int, default=0, help="sequence positions of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build covers one GPU's share of the work only (no collectives are built); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2104_04473_amd import binding as B      # raises if libptdp.so is missing: no fallback
+    from paper_2104_04473_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = WORKLOADS[args.workload]
+    n_chunks = w.get("chunks", 1)
+    m = w.get("m", 1)
+    cfg = B.make_cfg(h=w["h"], a=w["a"], t=w["t"], s=w["s"], b=w["b"], dtype=B.BF16, p_hidden=0.1, seed=0)
+    B.check(B.ptdp_cfg_validate(C.byref(cfg)), "cfg")
+    shape = (w["s"], w["b"], w["h"])
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    # ---- resident state -------------------------------------------------------------------------
+    chunks, params, grads = [], [], []
+    for c in range(n_chunks):
+        first = w["layers"] * (c * w.get("p", 1) + w.get("rank", 0))
+        ch = B.Chunk(cfg, w["layers"], first)
+        for l in range(w["layers"]):
+            P = synth.layer_params(w["h"], w["a"], w["t"], B.BF16, seed=1000 + first + l, device=dev, zero_bias=True,
+                                   ln_jitter=0.0)
+            G = synth.zero_grads(w["h"], w["a"], w["t"], dev)
+            ch.bind(l, P, G)
+            params.append(P)
+            grads.append(G)
+        chunks.append(ch)
+    slot_bytes = chunks[0].stash_bytes()
+    ws = torch.empty(chunks[0].workspace_bytes(), dtype=torch.uint8, device=dev)
+    n_pairs = n_chunks * m
+    xin = [synth.activations(*shape, B.BF16, seed=10 + i, device=dev) for i in range(n_pairs)]
+    dout = [synth.activations(*shape, B.BF16, seed=500 + i, device=dev) for i in range(n_pairs)]
+    yout = [torch.empty_like(xin[0]) for _ in range(n_pairs)]
+    din = [torch.empty_like(xin[0]) for _ in range(n_pairs)]
+
+    if args.workload == "c5":
+        steps = B.schedule_build(w["p"], n_chunks, m, w["rank"])
+        n_slots = B.ptdp_schedule_peak_inflight(w["p"], n_chunks, m, w["rank"])
+        pool = torch.empty(slot_bytes * n_slots, dtype=torch.uint8, device=dev)
+        arr = lambda ts: (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+        handles = (C.c_void_p * n_chunks)(*[c.handle for c in chunks])
+        a_in, a_out, a_dout, a_din = arr(xin), arr(yout), arr(dout), arr(din)
+
+        def step():
+            B.check(B.ptdp_schedule_run(handles, n_chunks, m, steps, len(steps), a_in, a_out, a_dout, a_din,
+                                        pool.data_ptr(), slot_bytes, n_slots, ws.data_ptr(), sh), "schedule_run")
+        passes_per_step = n_pairs
+    else:
+        pool = torch.empty(slot_bytes, dtype=torch.uint8, device=dev)
+
+        def step():
+            B.check(chunks[0].forward(0, xin[0].data_ptr(), yout[0].data_ptr(), pool.data_ptr(), ws.data_ptr(), stream),
+                    "chunk_forward")
+            B.check(chunks[0].backward(0, dout[0].data_ptr(), din[0].data_ptr(), pool.data_ptr(), ws.data_ptr(), stream),
+                    "chunk_backward")
+        passes_per_step = 1
+
+    flops_step = 3 * B.ptdp_layer_flops_fwd(C.byref(cfg)) * w["layers"] * passes_per_step
+    torch.cuda.synchronize()
+    peak_hbm_bytes = torch.cuda.memory_allocated()
+
+    # ---- timed region ---------------------------------------------------------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    tflops = flops_step * args.steps / dt / 1e12
+
+    # ---- per-kernel pass: HIP event pairs on the launch stream around every launch ------------------
+    B.ptdp_prof_enable(1)
+    prof_steps = max(1, min(args.steps, 3))
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    prof = B.prof_collect()
+    B.ptdp_prof_enable(0)
+    kernels = {}
+    for name, (ms, work, launches) in prof.items():
+        if launches == 0:
+            continue
+        is_flops = name.startswith("gemm") or name.startswith("attn")
+        rate = work / (ms * 1e-3) / (1e12 if is_flops else 1e9)
+        peak = PEAK_BF16_TFLOPS if is_flops else PEAK_HBM_GBS
+        kernels[name] = {"ms_per_step": round(ms / prof_steps, 4), "launches_per_step": launches // prof_steps,
+                         "avg_launch_ms": round(ms / launches, 5), "achieved": round(rate, 2),
+                         "unit": "TFLOP/s" if is_flops else "GB/s", "frac": round(rate / peak, 4)}
+    gemm = {k: v for k, v in prof.items() if k.startswith("gemm") and v[2] > 0}
+    dom = max(gemm, key=lambda k: gemm[k][0])
+    dms, dwork, dl = gemm[dom]
+    all_ms = sum(v[0] for v in gemm.values())
+    all_work = sum(v[1] for v in gemm.values())
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dwork / (dms * 1e-3) / 1e12, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(dwork / (dms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                "traffic": None, "flops_per_launch": dwork / dl, "avg_launch_ms": round(dms / dl, 5),
+                "all_gemm_achieved": round(all_work / (all_ms * 1e-3) / 1e12, 2),
+                "all_gemm_share_of_step": round(all_ms / prof_steps / ms_per_step, 4)}
+
+    # ---- CPU oracle on a bounded sample of the same workload ------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, params[0], args.cpu_sample_positions)
+
+    out = {
+        "metric": "model_tflops_per_gpu_fwd_bwd", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "config": {"workload": "%s: %s" % (args.workload, w["desc"]), "h": w["h"], "a": w["a"], "t": w["t"],
+                   "s": w["s"], "b": w["b"], "layers": w["layers"], "chunks": n_chunks, "microbatches": m,
+                   "dropout_p": 0.1, "model_flops_per_step": flops_step, "flop_factor": 3,
+                   "resident_hbm_gb": round(peak_hbm_bytes / 2 ** 30, 2)},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "context": "paper: 163 TFLOP/s per A100 = 52% of peak, end-to-end on 3072 GPUs, recompute counted (x4)",
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(w, params_dev, positions):
+    """Times the oracle (fp64 numpy, as it stands) on one layer forward+backward at the workload's
+    h, a, t, b, restricted to the first `positions` sequence positions."""
+    import numpy as np
+    from oracle import gpt_layer as L
+    from oracle import flops as F
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    if positions <= 0:
+        # aim at roughly 10-30 s: ~3 x 24 b s h^2 / t FLOPs at O(100) GFLOP/s fp64
+        target = 1.5e12
+        per_pos = 3 * 24 * w["b"] * w["h"] ** 2 / w["t"]
+        positions = int(max(16, min(w["s"], target // per_pos)))
+    cfg = L.LayerConfig(h=w["h"], a=w["a"], t=w["t"], s=positions, b=w["b"], p_hidden=0.1, seed=0)
+    P = {k: v.float().cpu().numpy() for k, v in params_dev.items()}
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((positions, w["b"], w["h"]))
+    dy = rng.standard_normal((positions, w["b"], w["h"]))
+    t0 = time.perf_counter()
+    y, cache = L.layer_forward(x, P, cfg, 0, 0)
+    dx, G = L.layer_backward(dy, P, cfg, cache)
+    dt = time.perf_counter() - t0
+    fl = F.shard_layer_flops(w["b"], positions, w["h"], w["t"])
+    return {"value": round(fl / dt / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": "1 layer forward+backward, fp64 numpy, first %d of %d sequence positions, same h/a/t/b" % (positions, w["s"])}
+
+
+if __name__ == "__main__":
+    main()

@@ -7,6 +7,10 @@ Pointers are passed as integers (``tensor.data_ptr()``), streams as the integer 
 import ctypes as C
 import os
 
+# torch ships its own HIP runtime; it must be the one already loaded when libptdp.so is opened, so
+# that the library and the tensors / streams it is handed live in the same runtime.
+import torch  # noqa: F401  (device memory and streams only)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libptdp.so")
 
