@@ -202,6 +202,83 @@ __device__ __forceinline__ void transpose8x8_b16(const uint4 (&in)[8], uint4 (&o
   }
 }
 
+// Cooperative (256 threads) staging of a 64-row tile of one head: rows row0 .. row0+63 of `src`
+// (row stride rs elements, DH columns), rows >= s zero-filled.
+//   direct:     lds[row][dh], KSTRIDE bytes per row
+//   transposed: lds[dh][row], kVtStride bytes per row (8x8 register transposes)
+template <int DH>
+__device__ __forceinline__ void stage_direct(char* lds, const bf16_t* __restrict__ src, size_t rs, int row0, int s) {
+  constexpr int KSTRIDE = DH * 2 + 16;
+  for (int v = threadIdx.x; v < kBKV * (DH / 8); v += 256) {
+    const int row = v / (DH / 8), ch = v % (DH / 8);
+    uint4 t = make_uint4(0, 0, 0, 0);
+    if (row0 + row < s) t = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + row) * rs + ch * 8);
+    *reinterpret_cast<uint4*>(lds + row * KSTRIDE + ch * 16) = t;
+  }
+}
+template <int DH>
+__device__ __forceinline__ void stage_transposed(char* lds, const bf16_t* __restrict__ src, size_t rs, int row0, int s) {
+  for (int blk = threadIdx.x; blk < 8 * (DH / 8); blk += 256) {
+    const int rg = blk & 7, dg = blk >> 3;
+    uint4 in[8], out[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int row = row0 + rg * 8 + r;
+      in[r] = row < s ? *reinterpret_cast<const uint4*>(src + (size_t)row * rs + dg * 8) : make_uint4(0, 0, 0, 0);
+    }
+    transpose8x8_b16(in, out);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) *reinterpret_cast<uint4*>(lds + (dg * 8 + r) * kVtStride + rg * 16) = out[r];
+  }
+}
+// MFMA A-operand fragment of a direct tile: row = lane & 31 (+32*sub), eight consecutive dh of k16 step kk.
+template <int DH>
+__device__ __forceinline__ bf16x8_t frag_direct(const char* lds, int sub, int kk, int l31, int half) {
+  constexpr int KSTRIDE = DH * 2 + 16;
+  return *reinterpret_cast<const bf16x8_t*>(lds + (sub * 32 + l31) * KSTRIDE + (kk * 2 + half) * 16);
+}
+// MFMA A-operand fragment of a transposed tile: row = dh index d*32 + (lane & 31); its eight tile rows
+// (keys or queries) are taken in the order of the 32x32 accumulator rows that feed the B operand:
+// 16*ks + 4*half + 0..3 and 16*ks + 8 + 4*half + 0..3 inside 32-row half `sub`.
+__device__ __forceinline__ bf16x8_t frag_transposed(const char* lds, int d, int sub, int ks, int l31, int half) {
+  const char* row = lds + (d * 32 + l31) * kVtStride + (sub * 32 + ks * 16 + 4 * half) * 2;
+  const uint2 lo = *reinterpret_cast<const uint2*>(row);
+  const uint2 hi = *reinterpret_cast<const uint2*>(row + 16);
+  uint4 t = make_uint4(lo.x, lo.y, hi.x, hi.y);
+  return *reinterpret_cast<bf16x8_t*>(&t);
+}
+// Registers 8*ks .. 8*ks+7 of a 32x32 accumulator as a bf16 B-operand fragment.
+__device__ __forceinline__ bf16x8_t pack_frag(const f32x16_t& a, int ks) {
+  uint4 t = make_uint4(pack_bf16x2(a[ks * 8 + 0], a[ks * 8 + 1]), pack_bf16x2(a[ks * 8 + 2], a[ks * 8 + 3]),
+                       pack_bf16x2(a[ks * 8 + 4], a[ks * 8 + 5]), pack_bf16x2(a[ks * 8 + 6], a[ks * 8 + 7]));
+  return *reinterpret_cast<bf16x8_t*>(&t);
+}
+__device__ __forceinline__ f32x16_t zero16() {
+  f32x16_t z;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) z[r] = 0.f;
+  return z;
+}
+// lane's 8 consecutive dh (k16 step kk) of one token row, as a B-operand fragment straight from HBM
+__device__ __forceinline__ bf16x8_t frag_global(const bf16_t* row_or_null, int kk, int half) {
+  uint4 t = make_uint4(0, 0, 0, 0);
+  if (row_or_null) t = *reinterpret_cast<const uint4*>(row_or_null + kk * 16 + half * 8);
+  return *reinterpret_cast<bf16x8_t*>(&t);
+}
+// accumulator rows (dh) of lane's column (token) -> 8-byte stores of 4 consecutive dh
+template <int NDT>
+__device__ __forceinline__ void store_cols(bf16_t* out_row, const f32x16_t (&acc)[NDT], float mul, int half) {
+#pragma unroll
+  for (int d = 0; d < NDT; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint2 w;
+      w.x = pack_bf16x2(acc[d][4 * g] * mul, acc[d][4 * g + 1] * mul);
+      w.y = pack_bf16x2(acc[d][4 * g + 2] * mul, acc[d][4 * g + 3] * mul);
+      *reinterpret_cast<uint2*>(out_row + d * 32 + 8 * g + 4 * half) = w;
+    }
+}
+
 template <int DH>
 __global__ void __launch_bounds__(256)
 attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* __restrict__ lse, int s, int b,
@@ -225,17 +302,11 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
   // Q^T fragments (B operand): lane = query, 8 consecutive dh per k16 step
   bf16x8_t qf[NKK];
 #pragma unroll
-  for (int kk = 0; kk < NKK; ++kk) {
-    uint4 t = make_uint4(0, 0, 0, 0);
-    if (my_q < s) t = *reinterpret_cast<const uint4*>(base + (size_t)my_q * rs + kk * 16 + half * 8);
-    qf[kk] = *reinterpret_cast<bf16x8_t*>(&t);
-  }
+  for (int kk = 0; kk < NKK; ++kk) qf[kk] = frag_global(my_q < s ? base + (size_t)my_q * rs : nullptr, kk, half);
 
   f32x16_t o[NDT];
 #pragma unroll
-  for (int d = 0; d < NDT; ++d)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+  for (int d = 0; d < NDT; ++d) o[d] = zero16();
   float m_run = -INFINITY, l_run = 0.f;
 
   const int q_last_blk = min(s, (qblk + 1) * kBQ) - 1;
@@ -243,27 +314,8 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
   for (int kt = 0; kt < ntiles; ++kt) {
     const int key0 = kt * kBKV;
     __syncthreads();
-    // K tile, direct: 64 keys x DH/8 chunks
-    for (int v = threadIdx.x; v < kBKV * (DH / 8); v += 256) {
-      const int key = v / (DH / 8), ch = v % (DH / 8);
-      uint4 t = make_uint4(0, 0, 0, 0);
-      if (key0 + key < s) t = *reinterpret_cast<const uint4*>(base + (size_t)(key0 + key) * rs + hp + ch * 8);
-      *reinterpret_cast<uint4*>(k_lds + key * KSTRIDE + ch * 16) = t;
-    }
-    // V tile, transposed into [dh][key]: 8x8 blocks, 8 key groups x DH/8 dh groups
-    for (int blk = threadIdx.x; blk < 8 * (DH / 8); blk += 256) {
-      const int kg = blk & 7, dg = blk >> 3;
-      uint4 in[8], out[8];
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const int key = key0 + kg * 8 + r;
-        in[r] = key < s ? *reinterpret_cast<const uint4*>(base + (size_t)key * rs + 2 * hp + dg * 8)
-                        : make_uint4(0, 0, 0, 0);
-      }
-      transpose8x8_b16(in, out);
-#pragma unroll
-      for (int r = 0; r < 8; ++r) *reinterpret_cast<uint4*>(vt_lds + (dg * 8 + r) * kVtStride + kg * 16) = out[r];
-    }
+    stage_direct<DH>(k_lds, base + hp, rs, key0, s);
+    stage_transposed<DH>(vt_lds, base + 2 * hp, rs, key0, s);
     __syncthreads();
     if (key0 > q_first + 31) continue;  // every key of the tile is in this wave's future
 
@@ -271,14 +323,11 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
     f32x16_t sacc[2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
+      sacc[sub] = zero16();
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[sub][r] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < NKK; ++kk) {
-        const bf16x8_t kf =
-            *reinterpret_cast<const bf16x8_t*>(k_lds + (sub * 32 + l31) * KSTRIDE + (kk * 2 + half) * 16);
-        sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[sub], 0, 0, 0);
-      }
+      for (int kk = 0; kk < NKK; ++kk)
+        sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(k_lds, sub, kk, l31, half), qf[kk],
+                                                            sacc[sub], 0, 0, 0);
     }
     // causal mask (also hides keys >= s, which are > every valid query) and running max
     const bool need_mask = key0 + kBKV - 1 > q_first;
@@ -302,50 +351,240 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
     // P^T as B operand: registers 8*ks .. 8*ks+7 of each half tile serve k16 step ks
     bf16x8_t pf[2][2];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+    for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        uint32_t w[4];
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          const float p0 = exp2f((sacc[sub][ks * 8 + 2 * d] - mx) * c2);
-          const float p1 = exp2f((sacc[sub][ks * 8 + 2 * d + 1] - mx) * c2);
-          l_run += p0 + p1;
-          w[d] = pack_bf16x2(p0, p1);
-        }
-        uint4 t = make_uint4(w[0], w[1], w[2], w[3]);
-        pf[sub][ks] = *reinterpret_cast<bf16x8_t*>(&t);
+      for (int r = 0; r < 16; ++r) {
+        sacc[sub][r] = exp2f((sacc[sub][r] - mx) * c2);
+        l_run += sacc[sub][r];
       }
-    // O^T[dh][query] += V^T[dh][key] P^T[key][query]; the A operand takes its 8 keys in the same order
-    // as the accumulator rows above: keys 16*ks + 4*half + 0..3 and 16*ks + 8 + 4*half + 0..3.
+      pf[sub][0] = pack_frag(sacc[sub], 0);
+      pf[sub][1] = pack_frag(sacc[sub], 1);
+    }
+    // O^T[dh][query] += V^T[dh][key] P^T[key][query]
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(vt_lds, d, sub, ks, l31, half), pf[sub][ks],
+                                                         o[d], 0, 0, 0);
+  }
+  l_run += __shfl_xor(l_run, 32, 64);
+  if (my_q < s) {
+    store_cols<NDT>(ctx + ((size_t)my_q * b + j) * hp + (size_t)e * DH, o, 1.f / l_run, half);
+    if (half == 0) lse[((size_t)j * heads + e) * s + my_q] = m_run * rsqrtf((float)DH) + __logf(l_run);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// bf16 MFMA backward.  P is recomputed from the stashed log-sum-exp; two kernels so that no result
+// needs atomics: one owns 128 queries and produces dQ, one owns 128 keys and produces dK and dV.
+//   dP = dO V^T, dS = P o (dP - delta), dQ = dS K / sqrt(dh), dK = dS^T Q / sqrt(dh), dV = P^T dO
+// ------------------------------------------------------------------------------------------------
+template <int DH>
+__global__ void __launch_bounds__(256)
+attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
+                 const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads) {
+  constexpr int KSTRIDE = DH * 2 + 16, NKK = DH / 16, NDT = DH / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* k_lds = smem;                         // K   [key][dh]
+  char* v_lds = k_lds + kBKV * KSTRIDE;       // V   [key][dh]
+  char* kt_lds = v_lds + kBKV * KSTRIDE;      // K^T [dh][key]
+
+  const int qblk = gridDim.x - 1 - blockIdx.x;
+  const int e = blockIdx.y, j = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
+  const int hp = heads * DH;
+  const size_t rs = (size_t)b * 3 * hp;
+  const bf16_t* base = qkv + (size_t)j * 3 * hp + (size_t)e * DH;
+  const int q_first = qblk * kBQ + wave * 32;
+  const int my_q = q_first + l31;
+  const bool valid = my_q < s;
+  const float scale = rsqrtf((float)DH), c2 = scale * 1.4426950408889634f;
+  const size_t stat = ((size_t)j * heads + e) * s + my_q;
+  const float L2 = valid ? lse[stat] * 1.4426950408889634f : 0.f;
+  const float D = valid ? delta[stat] : 0.f;
+
+  bf16x8_t qf[NKK], dof[NKK];
+  const bf16_t* dorow = dctx + ((size_t)my_q * b + j) * hp + (size_t)e * DH;
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) {
+    qf[kk] = frag_global(valid ? base + (size_t)my_q * rs : nullptr, kk, half);
+    dof[kk] = frag_global(valid ? dorow : nullptr, kk, half);
+  }
+  f32x16_t acc[NDT];
+#pragma unroll
+  for (int d = 0; d < NDT; ++d) acc[d] = zero16();
+
+  const int q_last_blk = min(s, (qblk + 1) * kBQ) - 1;
+  const int ntiles = q_last_blk / kBKV + 1;
+  for (int kt = 0; kt < ntiles; ++kt) {
+    const int key0 = kt * kBKV;
+    __syncthreads();
+    stage_direct<DH>(k_lds, base + hp, rs, key0, s);
+    stage_direct<DH>(v_lds, base + 2 * hp, rs, key0, s);
+    stage_transposed<DH>(kt_lds, base + hp, rs, key0, s);
+    __syncthreads();
+    if (key0 > q_first + 31) continue;
+    bf16x8_t dsf[2][2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      f32x16_t sacc = zero16(), dp = zero16();
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(k_lds, sub, kk, l31, half), qf[kk], sacc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(v_lds, sub, kk, l31, half), dof[kk], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const float p = key > my_q ? 0.f : exp2f(sacc[r] * c2 - L2);
+        sacc[r] = p * (dp[r] - D);
+      }
+      dsf[sub][0] = pack_frag(sacc, 0);
+      dsf[sub][1] = pack_frag(sacc, 1);
+    }
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+          acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(kt_lds, d, sub, ks, l31, half), dsf[sub][ks],
+                                                           acc[d], 0, 0, 0);
+  }
+  if (valid) store_cols<NDT>(dqkv + (size_t)my_q * rs + (size_t)j * 3 * hp + (size_t)e * DH, acc, scale, half);
+}
+
+template <int DH>
+__global__ void __launch_bounds__(256)
+attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
+                  const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads) {
+  constexpr int KSTRIDE = DH * 2 + 16, NKK = DH / 16, NDT = DH / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* q_lds = smem;                          // Q    [query][dh]
+  char* do_lds = q_lds + kBKV * KSTRIDE;       // dO   [query][dh]
+  char* qt_lds = do_lds + kBKV * KSTRIDE;      // Q^T  [dh][query]
+  char* dot_lds = qt_lds + DH * kVtStride;     // dO^T [dh][query]
+  float* lse_lds = reinterpret_cast<float*>(dot_lds + DH * kVtStride);  // lse * log2(e), +inf past the end
+  float* delta_lds = lse_lds + kBKV;
+
+  const int kblk = blockIdx.x;  // the first key blocks see the most queries and start first
+  const int e = blockIdx.y, j = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
+  const int hp = heads * DH;
+  const size_t rs = (size_t)b * 3 * hp;
+  const bf16_t* base = qkv + (size_t)j * 3 * hp + (size_t)e * DH;
+  const bf16_t* dobase = dctx + (size_t)j * hp + (size_t)e * DH;
+  const size_t dors = (size_t)b * hp;
+  const int key_first = kblk * kBQ + wave * 32;
+  const int my_key = key_first + l31;
+  const bool valid = my_key < s;
+  const float scale = rsqrtf((float)DH), c2 = scale * 1.4426950408889634f;
+  const float* lse_h = lse + ((size_t)j * heads + e) * s;
+  const float* delta_h = delta + ((size_t)j * heads + e) * s;
+
+  bf16x8_t kf[NKK], vf[NKK];
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) {
+    kf[kk] = frag_global(valid ? base + (size_t)my_key * rs + hp : nullptr, kk, half);
+    vf[kk] = frag_global(valid ? base + (size_t)my_key * rs + 2 * hp : nullptr, kk, half);
+  }
+  f32x16_t dk[NDT], dv[NDT];
+#pragma unroll
+  for (int d = 0; d < NDT; ++d) {
+    dk[d] = zero16();
+    dv[d] = zero16();
+  }
+  const int nq_tiles = (s + kBKV - 1) / kBKV;
+  for (int qt = (kblk * kBQ) / kBKV; qt < nq_tiles; ++qt) {
+    const int q0 = qt * kBKV;
+    __syncthreads();
+    stage_direct<DH>(q_lds, base, rs, q0, s);
+    stage_direct<DH>(do_lds, dobase, dors, q0, s);
+    stage_transposed<DH>(qt_lds, base, rs, q0, s);
+    stage_transposed<DH>(dot_lds, dobase, dors, q0, s);
+    if (threadIdx.x < kBKV) {
+      const int q = q0 + threadIdx.x;
+      lse_lds[threadIdx.x] = q < s ? lse_h[q] * 1.4426950408889634f : INFINITY;
+      delta_lds[threadIdx.x] = q < s ? delta_h[q] : 0.f;
+    }
+    __syncthreads();
+    if (q0 + kBKV - 1 < key_first) continue;  // every query of the tile precedes this wave's keys
+    bf16x8_t pf[2][2], dsf[2][2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      f32x16_t sacc = zero16(), dp = zero16();
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(q_lds, sub, kk, l31, half), kf[kk], sacc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(do_lds, sub, kk, l31, half), vf[kk], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int ql = sub * 32 + 8 * g + 4 * half;  // local index of the first of 4 consecutive queries
+        const float4 L4 = *reinterpret_cast<const float4*>(lse_lds + ql);
+        const float4 D4 = *reinterpret_cast<const float4*>(delta_lds + ql);
+        const float Ls[4] = {L4.x, L4.y, L4.z, L4.w}, Ds[4] = {D4.x, D4.y, D4.z, D4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = 4 * g + i;
+          const float p = my_key > q0 + ql + i ? 0.f : exp2f(sacc[r] * c2 - Ls[i]);
+          sacc[r] = p;
+          dp[r] = p * (dp[r] - Ds[i]);
+        }
+      }
+      pf[sub][0] = pack_frag(sacc, 0);
+      pf[sub][1] = pack_frag(sacc, 1);
+      dsf[sub][0] = pack_frag(dp, 0);
+      dsf[sub][1] = pack_frag(dp, 1);
+    }
 #pragma unroll
     for (int d = 0; d < NDT; ++d)
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-          const char* row = vt_lds + (d * 32 + l31) * kVtStride + (sub * 32 + ks * 16 + 4 * half) * 2;
-          uint2 lo = *reinterpret_cast<const uint2*>(row);
-          uint2 hi = *reinterpret_cast<const uint2*>(row + 16);
-          uint4 t = make_uint4(lo.x, lo.y, hi.x, hi.y);
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8_t*>(&t), pf[sub][ks], o[d], 0, 0, 0);
+          dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(dot_lds, d, sub, ks, l31, half), pf[sub][ks],
+                                                          dv[d], 0, 0, 0);
+          dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(qt_lds, d, sub, ks, l31, half), dsf[sub][ks],
+                                                          dk[d], 0, 0, 0);
         }
   }
-  l_run += __shfl_xor(l_run, 32, 64);
-  if (my_q < s) {
-    const float inv = 1.f / l_run;
-    bf16_t* out = ctx + ((size_t)my_q * b + j) * hp + (size_t)e * DH;
-#pragma unroll
-    for (int d = 0; d < NDT; ++d)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        uint2 w;
-        w.x = pack_bf16x2(o[d][4 * g] * inv, o[d][4 * g + 1] * inv);
-        w.y = pack_bf16x2(o[d][4 * g + 2] * inv, o[d][4 * g + 3] * inv);
-        *reinterpret_cast<uint2*>(out + d * 32 + 8 * g + 4 * half) = w;
-      }
-    if (half == 0) lse[((size_t)j * heads + e) * s + my_q] = m_run * rsqrtf((float)DH) + __logf(l_run);
+  if (valid) {
+    bf16_t* out = dqkv + (size_t)my_key * rs + (size_t)j * 3 * hp + (size_t)e * DH;
+    store_cols<NDT>(out + hp, dk, scale, half);
+    store_cols<NDT>(out + 2 * hp, dv, 1.f, half);
   }
+}
+
+// delta[j][e][i] = sum_d dctx[i][j][e][d] * ctx[i][j][e][d]; one wave per (token, head), 4 per block
+__global__ void __launch_bounds__(256)
+attn_delta_bf16(const bf16_t* __restrict__ ctx, const bf16_t* __restrict__ dctx, float* __restrict__ delta, int s, int b,
+                int heads, int dh) {
+  const int lane = threadIdx.x & 63;
+  const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // (token, head) pair index
+  const size_t nrows = (size_t)s * b * heads;
+  if (row >= nrows) return;
+  const size_t tok = row / heads;
+  const int e = (int)(row % heads);
+  const int i = (int)(tok / b), j = (int)(tok % b);
+  const bf16_t* c = ctx + row * dh;
+  const bf16_t* d = dctx + row * dh;
+  float a = 0.f;
+  for (int v = lane; v < dh / 8; v += 64) {
+    Vec16<bf16_t> x, y;
+    float xf[8], yf[8];
+    x.load(c + v * 8);
+    y.load(d + v * 8);
+    x.unpack(xf);
+    y.unpack(yf);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) a += xf[t] * yf[t];
+  }
+  a = wave_sum(a);
+  if (lane == 0) delta[((size_t)j * heads + e) * s + i] = a;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -391,15 +630,48 @@ static int attn_bwd_rowwise_t(const void* qkv, const void* ctx, const float* lse
   return PTDP_OK;
 }
 
+template <int DH>
+static int attn_bwd_mfma_t(const bf16_t* qkv, const bf16_t* ctx, const float* lse, const bf16_t* dctx, bf16_t* dqkv,
+                           float* delta, int s, int b, int heads, hipStream_t stream) {
+  constexpr int KSTRIDE = DH * 2 + 16;
+  constexpr int smem_dq = 2 * kBKV * KSTRIDE + DH * kVtStride;
+  constexpr int smem_dkv = 2 * kBKV * KSTRIDE + 2 * DH * kVtStride + 2 * kBKV * (int)sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq_mfma<DH>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem_dq) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem_dkv) != hipSuccess)
+      return PTDP_E_HIP;
+    attr_set = true;
+  }
+  const size_t rows = (size_t)s * b * heads;
+  hipLaunchKernelGGL(attn_delta_bf16, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, ctx, dctx, delta, s, b,
+                     heads, DH);
+  const dim3 grid((s + kBQ - 1) / kBQ, heads, b);
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH>), grid, dim3(256), smem_dkv, stream, qkv, dctx, lse, delta, dqkv, s, b, heads);
+  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH>), grid, dim3(256), smem_dq, stream, qkv, dctx, lse, delta, dqkv, s, b, heads);
+  return PTDP_OK;
+}
+
 int launch_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
                     float* delta, int s, int b, int heads, int dh, hipStream_t stream) {
   if (s == 0 || b == 0 || heads == 0) return PTDP_OK;
   if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
   Launch L(PTDP_K_ATTN_BWD, 2.0 * attn_flops(s, b, heads, dh), stream);
-  if (dtype == PTDP_F32)
-    attn_bwd_rowwise_t<float>(qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, stream);
-  else
-    attn_bwd_rowwise_t<bf16_t>(qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, stream);
+  int rc = PTDP_OK;
+  if (dtype == PTDP_F32) {
+    rc = attn_bwd_rowwise_t<float>(qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, stream);
+  } else {
+    const bf16_t* q = (const bf16_t*)qkv;
+    const bf16_t* c = (const bf16_t*)ctx;
+    const bf16_t* d = (const bf16_t*)dctx;
+    bf16_t* o = (bf16_t*)dqkv;
+    if (dh == 64) rc = attn_bwd_mfma_t<64>(q, c, lse, d, o, delta, s, b, heads, stream);
+    else if (dh == 128) rc = attn_bwd_mfma_t<128>(q, c, lse, d, o, delta, s, b, heads, stream);
+    else rc = attn_bwd_mfma_t<160>(q, c, lse, d, o, delta, s, b, heads, stream);
+  }
+  if (rc != PTDP_OK) return rc;
   return L.status();
 }
 
