@@ -237,6 +237,202 @@ gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, voi
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// bf16 MFMA kernel, second generation: global -> LDS without passing through registers
+// (buffer_load ... lds, 16 bytes per lane), 256 x 256 x 64 block tile, 8 waves (2 x 4, 128 x 64 each),
+// two LDS stages.  Out-of-range lanes use an offset beyond the buffer's num_records, for which the
+// hardware returns zeros.
+//
+// LDS tile layouts (32 KiB each):
+//   k-contiguous operand: [row][8 chunks of 16 B]; chunk c of row r sits in slot c ^ (r & 7).
+//   k-slow operand (memory [k][row]): [k][32 chunks of 16 B] (512 B per k); chunk c of k-row k sits in
+//     slot c ^ (4 * (k & 3)).  MFMA fragments are gathered with ds_read_b64_tr_b16: within 16 lanes,
+//     lane i receives element (i & 3) of the 8-byte rows addressed by lanes (i >> 2) + {0, 4, 8, 12}.
+// ------------------------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+constexpr uint32_t kOob = 0x80000000u;  // beyond any num_records this kernel accepts (< 2 GiB)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+
+// one wave-wide 1 KiB load into LDS at `dst` (wave-uniform); lane i lands at dst + 16*i
+__device__ __forceinline__ void load_lds_16(__amdgpu_buffer_rsrc_t r, char* dst, uint32_t voff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_t*)dst, 16, voff, 0, 0, 0);
+}
+
+template <bool KSLOW> struct TileLoad {
+  // per-lane state of the 4 wave-loads this wave issues per tile
+  uint32_t off[4];   // byte offset of the lane's chunk at k-tile 0, or kOob if its row is out of range
+  int kpos[4];       // k index (k-slow) or first k of the chunk (k-contiguous) inside the tile
+  uint32_t kstep;    // byte advance per k-tile
+
+  // base points at the block's first row (k-contiguous: base + row0*ld; k-slow: base + row0)
+  __device__ __forceinline__ void init(size_t ld, int rows_left, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int li = wave * 4 + i;
+      if (!KSLOW) {
+        const int row = li * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ (row & 7);
+        kpos[i] = chunk * 8;
+        off[i] = row < rows_left ? (uint32_t)(((size_t)row * ld + chunk * 8) * 2) : kOob;
+      } else {
+        const int k = li * 2 + (lane >> 5);
+        const int chunk = (lane & 31) ^ (4 * (k & 3));
+        kpos[i] = k;
+        off[i] = chunk * 8 < rows_left ? (uint32_t)(((size_t)k * ld + chunk * 8) * 2) : kOob;
+      }
+    }
+    kstep = KSLOW ? (uint32_t)(BK * ld * 2) : (uint32_t)(BK * 2);
+  }
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char* tile, int wave, int kt, int K) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bool ok = off[i] != kOob && kt * BK + kpos[i] < K;
+      load_lds_16(r, tile + (wave * 4 + i) * 1024, ok ? off[i] + (uint32_t)kt * kstep : kOob);
+    }
+  }
+};
+
+// MFMA operand fragment (row = tile row of this lane, 8 k of k16 step kk) from either layout
+template <bool KSLOW>
+__device__ __forceinline__ bf16x8_t read_frag(const char* tile, int row_base, int kk, int lane) {
+  if (!KSLOW) {
+    const int row = row_base + (lane & 31);
+    const int chunk = (kk * 2 + (lane >> 5)) ^ (row & 7);
+    return *reinterpret_cast<const bf16x8_t*>(tile + row * 128 + chunk * 16);
+  } else {
+    const int r = lane & 15, G = lane >> 4;
+    const int n0 = row_base + 16 * (G & 1) + 4 * (r & 3);
+    const int k = kk * 16 + 8 * (G >> 1) + (r >> 2);  // (k & 3) == r >> 2 for both halves
+    const int slot = (n0 >> 3) ^ (4 * (r >> 2));
+    const char* p = tile + k * 512 + slot * 16 + (n0 & 7) * 2;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p + 4 * 512));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
+    s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return *reinterpret_cast<bf16x8_t*>(&v);
+  }
+}
+
+template <bool TA, bool TB, bool OUT_F32>
+__global__ void __launch_bounds__(512)
+gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* Cv,
+                     const bf16_t* __restrict__ bias, int M, int N, int K, int accumulate) {
+  constexpr int BM = 256, BN = 256, WM = 128, WN = 64, TM = WM / 32, TN = WN / 32;
+  constexpr int TILE_BYTES = 256 * BK * 2, STAGE_BYTES = 2 * TILE_BYTES;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  const int tiles_m = (M + BM - 1) / BM;
+  const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const size_t lda = TA ? (size_t)M : (size_t)K;
+  const size_t ldb = TB ? (size_t)N : (size_t)K;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm0 = (wave >> 2) * WM, wn0 = (wave & 3) * WN;
+
+  // buffer descriptors start at the block's first row so that lane offsets stay small
+  const bf16_t* a_base = TA ? A + m0 : A + (size_t)m0 * lda;
+  const bf16_t* b_base = TB ? B + n0 : B + (size_t)n0 * ldb;
+  const size_t a_total = (size_t)M * K * 2, b_total = (size_t)N * K * 2;
+  const size_t a_left = a_total - (size_t)(a_base - A) * 2, b_left = b_total - (size_t)(b_base - B) * 2;
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, (uint32_t)(a_left < 0x7fffffffu ? a_left : 0x7fffffffu));
+  const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, (uint32_t)(b_left < 0x7fffffffu ? b_left : 0x7fffffffu));
+
+  TileLoad<TA> la;
+  TileLoad<TB> lb;
+  la.init(lda, M - m0, wave, lane);
+  lb.init(ldb, N - n0, wave, lane);
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = (K + BK - 1) / BK;
+  la.issue(ra, smem, wave, 0, K);
+  lb.issue(rb, smem + TILE_BYTES, wave, 0, K);
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's LDS writes have landed
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const char* cur = smem + (kt & 1) * STAGE_BYTES;
+    char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+    if (kt + 1 < nk) {
+      la.issue(ra, nxt, wave, kt + 1, K);
+      lb.issue(rb, nxt + TILE_BYTES, wave, kt + 1, K);
+    }
+    bf16x8_t af[2][TM], bfr[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[0][i] = read_frag<TA>(cur, wm0 + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bfr[0][j] = read_frag<TB>(cur + TILE_BYTES, wn0 + j * 32, 0, lane);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const int c = kk & 1, n = c ^ 1;
+      if (kk + 1 < BK / 16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[n][i] = read_frag<TA>(cur, wm0 + i * 32, kk + 1, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[n][j] = read_frag<TB>(cur + TILE_BYTES, wn0 + j * 32, kk + 1, lane);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bfr[c][j], acc[i][j], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + wn0 + j * 32 + (lane & 31);
+    if (n >= N) continue;
+    const float bv = bias ? bf16_to_f32(bias[n]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m >= M) continue;
+        const float val = acc[i][j][r] + bv;
+        if (OUT_F32) {
+          float* c = reinterpret_cast<float*>(Cv) + (size_t)m * N + n;
+          *c = accumulate ? *c + val : val;
+        } else {
+          reinterpret_cast<bf16_t*>(Cv)[(size_t)m * N + n] = f32_to_bf16(val);
+        }
+      }
+    }
+  }
+}
+
+template <bool TA, bool TB, bool OUT_F32>
+static int launch_bf16_dtl(const void* A, const void* B, void* C, const void* bias, int M, int N, int K,
+                           int accumulate, hipStream_t st) {
+  auto kern = gemm_bf16_dtl_kernel<TA, TB, OUT_F32>;
+  constexpr int smem = 2 * 2 * 256 * BK * 2;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
+        hipSuccess)
+      return PTDP_E_HIP;
+    attr_set = true;
+  }
+  const int tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(512), smem, st, (const bf16_t*)A, (const bf16_t*)B, C,
+                     (const bf16_t*)bias, M, N, K, accumulate);
+  return PTDP_OK;
+}
+
 template <int BM, int BN, int WM, int WN, bool TA, bool TB, bool OUT_F32>
 static int launch_bf16_cfg(const void* A, const void* B, void* C, const void* bias, int M, int N, int K, int accumulate,
                            hipStream_t st) {
@@ -258,6 +454,12 @@ static int launch_bf16_cfg(const void* A, const void* B, void* C, const void* bi
 template <bool TA, bool TB>
 static int launch_bf16_mode(const void* A, const void* B, void* C, const void* bias, int M, int N, int K, int out_f32,
                             int accumulate, hipStream_t st) {
+  // the direct-to-LDS kernel addresses each operand through a 31-bit byte offset
+  const bool small = (size_t)M * K * 2 < 0x7fffffffull && (size_t)N * K * 2 < 0x7fffffffull && K > 0;
+  if (small) {
+    if (out_f32) return launch_bf16_dtl<TA, TB, true>(A, B, C, bias, M, N, K, accumulate, st);
+    return launch_bf16_dtl<TA, TB, false>(A, B, C, bias, M, N, K, accumulate, st);
+  }
   if (out_f32) return launch_bf16_cfg<256, 256, 128, 128, TA, TB, true>(A, B, C, bias, M, N, K, accumulate, st);
   return launch_bf16_cfg<256, 256, 128, 128, TA, TB, false>(A, B, C, bias, M, N, K, accumulate, st);
 }
