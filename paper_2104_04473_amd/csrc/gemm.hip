@@ -5,10 +5,9 @@
 //   mode NT: C[M,N] = A[M,K] B[N,K]^T        input grad   dX = dY W^T
 //   mode TN: C[M,N] = A[K,M]^T B[K,N]        weight grad  dW = X^T dY
 //
-// bf16 path: v_mfma_f32_32x32x16_bf16 (gfx950), 256 x 256 x 64 block tile, LDS double buffering,
-// register-staged global loads.  An operand whose reduction index is the slow memory index (B in NN,
-// both in TN) is transposed in registers (8 x 8 blocks of 16-bit values) on its way into LDS, so that
-// every MFMA fragment is one 16-byte LDS read of eight consecutive k.
+// bf16 path: v_mfma_f32_32x32x16_bf16 (gfx950), 256 x 256 block tile, multi-stage LDS ring filled by
+// direct global->LDS loads.  An operand whose reduction index is the slow memory index (B in NN, both
+// in TN) stays in its memory order in LDS and is gathered into MFMA fragments by transposing LDS reads.
 // fp32 path: a plain LDS-tiled FMA kernel (correctness configuration only).
 #include "common.h"
 
@@ -67,184 +66,14 @@ gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B, float*
 }
 
 // ------------------------------------------------------------------------------------------------
-// bf16 MFMA kernel
-// ------------------------------------------------------------------------------------------------
-constexpr int BK = 64;  // k per LDS stage: one 128-byte LDS row of eight 16-byte chunks
-
-// LDS tile: R rows (m or n index) x 64 k, 128 bytes per row; chunk c of row r sits at chunk
-// c ^ swz(r).  swz mixes bits 0-2 and 3-5 of the row so that (a) the 8 rows read by 8 neighbouring
-// lanes of a fragment load and (b) the 8 rows r0+j of neighbouring 8x8 transposed blocks fall into
-// different bank groups.
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ swz(row)) << 4); }
-
-// Stages one R x 64 operand tile through registers.
-//   TRANS = false: memory is [row][k] (k contiguous):  src + row*ld + k
-//   TRANS = true : memory is [k][row] (row contiguous): src + k*ld + row
-template <int R, bool TRANS> struct Stage {
-  static constexpr int NV = TRANS ? 8 * ((R + 255) / 256) : R / 32;
-  uint4 v[NV];
-
-  __device__ __forceinline__ void load(const bf16_t* __restrict__ src, size_t ld, int row0, int row_end, int k0,
-                                       int K) {
-    const int t = threadIdx.x;
-    if (!TRANS) {
-      const int chunk = t & 7;
-      const int k = k0 + chunk * 8;
-#pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int row = row0 + (t >> 3) + i * 32;
-        v[i] = (row < row_end && k < K) ? *reinterpret_cast<const uint4*>(src + (size_t)row * ld + k)
-                                        : make_uint4(0, 0, 0, 0);
-      }
-    } else {
-#pragma unroll
-      for (int blk = 0; blk < NV / 8; ++blk) {
-        const int id = t + blk * 256;  // 8x8 block id: R/8 row groups x 8 k groups
-        const int rg = id % (R / 8), kg = id / (R / 8);
-        const int row = row0 + rg * 8;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int k = k0 + kg * 8 + j;
-          v[blk * 8 + j] = (id < R && row < row_end && k < K)
-                               ? *reinterpret_cast<const uint4*>(src + (size_t)k * ld + row)
-                               : make_uint4(0, 0, 0, 0);
-        }
-      }
-    }
-  }
-
-  __device__ __forceinline__ void store(char* lds) const {
-    const int t = threadIdx.x;
-    if (!TRANS) {
-      const int chunk = t & 7;
-#pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int row = (t >> 3) + i * 32;
-        *reinterpret_cast<uint4*>(lds + lds_off(row, chunk)) = v[i];
-      }
-    } else {
-#pragma unroll
-      for (int blk = 0; blk < NV / 8; ++blk) {
-        const int id = t + blk * 256;
-        if (id >= R) continue;
-        const int rg = id % (R / 8), kg = id / (R / 8);
-        // in[j] holds k = j, rows 0..7 (two per dword); out[r] must hold row r, k = 0..7
-        const uint32_t* in = reinterpret_cast<const uint32_t*>(&v[blk * 8]);  // in[j*4 + d]
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          uint32_t o[4];
-#pragma unroll
-          for (int d = 0; d < 4; ++d) {
-            const uint32_t x = in[(2 * d) * 4 + (r >> 1)], y = in[(2 * d + 1) * 4 + (r >> 1)];
-            o[d] = (r & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
-          }
-          *reinterpret_cast<uint4*>(lds + lds_off(rg * 8 + r, kg)) = make_uint4(o[0], o[1], o[2], o[3]);
-        }
-      }
-    }
-  }
-};
-
-// BM x BN block tile, waves arranged (BM/WM) x (BN/WN), each wave WM x WN = (WM/32) x (WN/32) MFMA tiles.
-template <int BM, int BN, int WM, int WN, bool TA, bool TB, bool OUT_F32>
-__global__ void __launch_bounds__((BM / WM) * (BN / WN) * 64)
-gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* Cv, const bf16_t* __restrict__ bias,
-                 int M, int N, int K, int accumulate) {
-  static_assert((BM / WM) * (BN / WN) == 4, "loaders assume 256 threads");
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
-  constexpr int TM = WM / 32, TN = WN / 32;
-
-  // tile order: consecutive blocks walk M first so that blocks running together share the B panel
-  const int tiles_m = (M + BM - 1) / BM;
-  const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const size_t lda = TA ? (size_t)M : (size_t)K;
-  const size_t ldb = TB ? (size_t)N : (size_t)K;   // TB: B is [K,N]; else B is [N,K]
-
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm0 = (wave / (BN / WN)) * WM, wn0 = (wave % (BN / WN)) * WN;
-
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  Stage<BM, TA> sa;
-  Stage<BN, TB> sb;
-  const int nk = (K + BK - 1) / BK;
-  sa.load(A, lda, m0, M, 0, K);
-  sb.load(B, ldb, n0, N, 0, K);
-  sa.store(smem);
-  sb.store(smem + A_BYTES);
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; ++kt) {
-    char* cur = smem + (kt & 1) * STAGE_BYTES;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-    if (kt + 1 < nk) {
-      sa.load(A, lda, m0, M, (kt + 1) * BK, K);
-      sb.load(B, ldb, n0, N, (kt + 1) * BK, K);
-    }
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8_t af[TM], bfr[TN];
-      const int chunk = kk * 2 + (lane >> 5);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8_t*>(cur + lds_off(wm0 + i * 32 + (lane & 31), chunk));
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8_t*>(cur + A_BYTES + lds_off(wn0 + j * 32 + (lane & 31), chunk));
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      sa.store(nxt);
-      sb.store(nxt + A_BYTES);
-    }
-    __syncthreads();
-  }
-
-  // epilogue.  32x32 accumulator layout: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane/32) + r%4.
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = n0 + wn0 + j * 32 + (lane & 31);
-    if (n >= N) continue;
-    const float bv = bias ? bf16_to_f32(bias[n]) : 0.f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m >= M) continue;
-        const float val = acc[i][j][r] + bv;
-        if (OUT_F32) {
-          float* c = reinterpret_cast<float*>(Cv) + (size_t)m * N + n;
-          *c = accumulate ? *c + val : val;
-        } else {
-          reinterpret_cast<bf16_t*>(Cv)[(size_t)m * N + n] = f32_to_bf16(val);
-        }
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// bf16 MFMA kernel, second generation: global -> LDS without passing through registers
-// (buffer_load ... lds, 16 bytes per lane), 256 x 256 x 64 block tile, 8 waves (2 x 4, 128 x 64 each),
-// two LDS stages.  Out-of-range lanes use an offset beyond the buffer's num_records, for which the
-// hardware returns zeros.
+// bf16 MFMA kernel: global -> LDS without passing through registers (buffer_load ... lds, 16 bytes
+// per lane), 256 x 256 x BKT block tile, 8 waves (2 x 4, 128 x 64 each), a ring of NST LDS stages.
+// Out-of-range lanes use an offset beyond the buffer's num_records, for which the hardware returns
+// zeros.
 //
-// LDS tile layouts (32 KiB each):
-//   k-contiguous operand: [row][8 chunks of 16 B]; chunk c of row r sits in slot c ^ (r & 7).
+// LDS tile layouts:
+//   k-contiguous operand: [row][BKT/8 chunks of 16 B]; chunk c of row r sits in slot c ^ f(r), f chosen
+//     so that 16 neighbouring rows of one fragment read fall into 16 different 16-byte bank groups.
 //   k-slow operand (memory [k][row]): [k][32 chunks of 16 B] (512 B per k); chunk c of k-row k sits in
 //     slot c ^ (4 * (k & 3)).  MFMA fragments are gathered with ds_read_b64_tr_b16: within 16 lanes,
 //     lane i receives element (i & 3) of the 8-byte rows addressed by lanes (i >> 2) + {0, 4, 8, 12}.
@@ -263,36 +92,45 @@ __device__ __forceinline__ void load_lds_16(__amdgpu_buffer_rsrc_t r, char* dst,
   __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_t*)dst, 16, voff, 0, 0, 0);
 }
 
-template <bool KSLOW> struct TileLoad {
-  // per-lane state of the 4 wave-loads this wave issues per tile
-  uint32_t off[4];   // byte offset of the lane's chunk at k-tile 0, or kOob if its row is out of range
-  int kpos[4];       // k index (k-slow) or first k of the chunk (k-contiguous) inside the tile
-  uint32_t kstep;    // byte advance per k-tile
+// One 256-row operand tile of 64 k (32 KiB) is filled by 32 wave-loads of 1 KiB; wave w of NW issues
+// wave-loads w*LPW .. w*LPW+LPW-1.
+constexpr int BK = 64;
+template <bool KSLOW, int NW> struct TileLoad {
+  static constexpr int LPW = 32 / NW;
+  uint32_t off[LPW];   // byte offset of the lane's chunk at k-tile 0, or kOob if its row is out of range
+  uint32_t kstep;      // byte advance per k-tile
+  int kfirst;          // k of wave-load 0's chunk (k-contiguous: first k of the chunk; k-slow: the k-row)
 
-  // base points at the block's first row (k-contiguous: base + row0*ld; k-slow: base + row0)
+  // the descriptor's base is the block's first row (k-contiguous: base + row0*ld; k-slow: base + row0)
   __device__ __forceinline__ void init(size_t ld, int rows_left, int wave, int lane) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int li = wave * 4 + i;
+    for (int i = 0; i < LPW; ++i) {
+      const int li = wave * LPW + i;
       if (!KSLOW) {
         const int row = li * 8 + (lane >> 3);
-        const int chunk = (lane & 7) ^ (row & 7);
-        kpos[i] = chunk * 8;
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
         off[i] = row < rows_left ? (uint32_t)(((size_t)row * ld + chunk * 8) * 2) : kOob;
       } else {
         const int k = li * 2 + (lane >> 5);
         const int chunk = (lane & 31) ^ (4 * (k & 3));
-        kpos[i] = k;
         off[i] = chunk * 8 < rows_left ? (uint32_t)(((size_t)k * ld + chunk * 8) * 2) : kOob;
       }
     }
     kstep = KSLOW ? (uint32_t)(BK * ld * 2) : (uint32_t)(BK * 2);
+    kfirst = KSLOW ? wave * LPW * 2 + (lane >> 5) : 0;
   }
-  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char* tile, int wave, int kt, int K) {
+  // k of the lane's data in wave-load i: k-contiguous -> depends on the row's swizzle, recomputed here
+  __device__ __forceinline__ int kpos(int i, int wave, int lane) const {
+    if (KSLOW) return kfirst + 2 * i;
+    const int row = (wave * LPW + i) * 8 + (lane >> 3);
+    return ((lane & 7) ^ ((row >> 1) & 7)) * 8;
+  }
+  // k-tiles past the end of K come back as zeros (every lane out of range)
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char* tile, int wave, int lane, int kt, int K) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const bool ok = off[i] != kOob && kt * BK + kpos[i] < K;
-      load_lds_16(r, tile + (wave * 4 + i) * 1024, ok ? off[i] + (uint32_t)kt * kstep : kOob);
+    for (int i = 0; i < LPW; ++i) {
+      const bool ok = off[i] != kOob && kt * BK + kpos(i, wave, lane) < K;
+      load_lds_16(r, tile + (wave * LPW + i) * 1024, ok ? off[i] + (uint32_t)kt * kstep : kOob);
     }
   }
 };
@@ -302,7 +140,7 @@ template <bool KSLOW>
 __device__ __forceinline__ bf16x8_t read_frag(const char* tile, int row_base, int kk, int lane) {
   if (!KSLOW) {
     const int row = row_base + (lane & 31);
-    const int chunk = (kk * 2 + (lane >> 5)) ^ (row & 7);
+    const int chunk = (kk * 2 + (lane >> 5)) ^ ((row >> 1) & 7);
     return *reinterpret_cast<const bf16x8_t*>(tile + row * 128 + chunk * 16);
   } else {
     const int r = lane & 15, G = lane >> 4;
@@ -318,21 +156,36 @@ __device__ __forceinline__ bf16x8_t read_frag(const char* tile, int row_base, in
   }
 }
 
-template <bool TA, bool TB, bool OUT_F32>
-__global__ void __launch_bounds__(512)
+// s_waitcnt vmcnt(0) only (gfx9 encoding: lgkmcnt and expcnt fields left at their maxima)
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+
+// WGM x WGN waves, each (256/WGM) x (256/WGN); two LDS stages; the loads of k-tile kt+1 are issued
+// while k-tile kt is multiplied.  Fragments are double-buffered in registers: the reads of k16 step
+// kk+1 (or of the next tile's step 0, after the barrier) are issued before the MFMAs of step kk.
+template <bool TA, bool TB, bool OUT_F32, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64)
 gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* Cv,
                      const bf16_t* __restrict__ bias, int M, int N, int K, int accumulate) {
-  constexpr int BM = 256, BN = 256, WM = 128, WN = 64, TM = WM / 32, TN = WN / 32;
-  constexpr int TILE_BYTES = 256 * BK * 2, STAGE_BYTES = 2 * TILE_BYTES;
+  constexpr int BM = 256, BN = 256, NW = WGM * WGN, WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  constexpr int TILE_BYTES = 256 * BK * 2, STAGE_BYTES = 2 * TILE_BYTES, NKK = BK / 16;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-  const int tiles_m = (M + BM - 1) / BM;
-  const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Each XCD owns the column
+  // tiles x, x+8, ... and works through them in groups of up to 8 row tiles, so that the
+  // workgroups resident on one XCD share 8 A panels and 4 B panels through that L2.
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int nx = (tiles_n + 7) / 8;                 // column tiles per XCD (some may be past the end)
+  const int per_group = 8 * nx;                     // blocks of one full group of 8 row tiles
+  const int grp = local / per_group, in_grp = local % per_group;
+  const int gm = min(8, tiles_m - grp * 8);         // row tiles in this group
+  const int tile_m = grp * 8 + in_grp % gm, tile_n = (in_grp / gm) * 8 + xcd;
+  if (tile_n >= tiles_n) return;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const size_t lda = TA ? (size_t)M : (size_t)K;
   const size_t ldb = TB ? (size_t)N : (size_t)K;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm0 = (wave >> 2) * WM, wn0 = (wave & 3) * WN;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
 
   // buffer descriptors start at the block's first row so that lane offsets stay small
   const bf16_t* a_base = TA ? A + m0 : A + (size_t)m0 * lda;
@@ -342,8 +195,8 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
   const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, (uint32_t)(a_left < 0x7fffffffu ? a_left : 0x7fffffffu));
   const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, (uint32_t)(b_left < 0x7fffffffu ? b_left : 0x7fffffffu));
 
-  TileLoad<TA> la;
-  TileLoad<TB> lb;
+  TileLoad<TA, NW> la;
+  TileLoad<TB, NW> lb;
   la.init(lda, M - m0, wave, lane);
   lb.init(ldb, N - n0, wave, lane);
 
@@ -356,31 +209,39 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = (K + BK - 1) / BK;
-  la.issue(ra, smem, wave, 0, K);
-  lb.issue(rb, smem + TILE_BYTES, wave, 0, K);
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's LDS writes have landed
+  la.issue(ra, smem, wave, lane, 0, K);
+  lb.issue(rb, smem + TILE_BYTES, wave, lane, 0, K);
+  wait_vmcnt0();
   __syncthreads();
+
+  bf16x8_t af[2][TM], bfr[2][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) af[0][i] = read_frag<TA>(smem, wm0 + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bfr[0][j] = read_frag<TB>(smem + TILE_BYTES, wn0 + j * 32, 0, lane);
 
   for (int kt = 0; kt < nk; ++kt) {
     const char* cur = smem + (kt & 1) * STAGE_BYTES;
     char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
-    if (kt + 1 < nk) {
-      la.issue(ra, nxt, wave, kt + 1, K);
-      lb.issue(rb, nxt + TILE_BYTES, wave, kt + 1, K);
-    }
-    bf16x8_t af[2][TM], bfr[2][TN];
+    // stage nxt was last read before the barrier that ended the previous iteration's reads
+    la.issue(ra, nxt, wave, lane, kt + 1, K);
+    lb.issue(rb, nxt + TILE_BYTES, wave, lane, kt + 1, K);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[0][i] = read_frag<TA>(cur, wm0 + i * 32, 0, lane);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[0][j] = read_frag<TB>(cur + TILE_BYTES, wn0 + j * 32, 0, lane);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
+    for (int kk = 0; kk < NKK; ++kk) {
       const int c = kk & 1, n = c ^ 1;
-      if (kk + 1 < BK / 16) {
+      if (kk + 1 < NKK) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) af[n][i] = read_frag<TA>(cur, wm0 + i * 32, kk + 1, lane);
 #pragma unroll
         for (int j = 0; j < TN; ++j) bfr[n][j] = read_frag<TB>(cur + TILE_BYTES, wn0 + j * 32, kk + 1, lane);
+      } else {
+        // every fragment of `cur` is in registers: the next tile may be consumed, `cur` may be refilled
+        wait_vmcnt0();
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[n][i] = read_frag<TA>(nxt, wm0 + i * 32, 0, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[n][j] = read_frag<TB>(nxt + TILE_BYTES, wn0 + j * 32, 0, lane);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -388,8 +249,6 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bfr[c][j], acc[i][j], 0, 0, 0);
     }
-    __builtin_amdgcn_s_waitcnt(0x0f70);
-    __syncthreads();
   }
 
 #pragma unroll
@@ -406,7 +265,10 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
         const float val = acc[i][j][r] + bv;
         if (OUT_F32) {
           float* c = reinterpret_cast<float*>(Cv) + (size_t)m * N + n;
-          *c = accumulate ? *c + val : val;
+          // every element is owned by one lane, so the L2-side add is as deterministic as a
+          // read-modify-write here would be, without the round trip
+          if (accumulate) unsafeAtomicAdd(c, val);
+          else *c = val;
         } else {
           reinterpret_cast<bf16_t*>(Cv)[(size_t)m * N + n] = f32_to_bf16(val);
         }
@@ -415,10 +277,15 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
   }
 }
 
+#ifndef PTDP_GEMM_WGM
+#define PTDP_GEMM_WGM 2
+#define PTDP_GEMM_WGN 4
+#endif
+
 template <bool TA, bool TB, bool OUT_F32>
 static int launch_bf16_dtl(const void* A, const void* B, void* C, const void* bias, int M, int N, int K,
                            int accumulate, hipStream_t st) {
-  auto kern = gemm_bf16_dtl_kernel<TA, TB, OUT_F32>;
+  auto kern = gemm_bf16_dtl_kernel<TA, TB, OUT_F32, PTDP_GEMM_WGM, PTDP_GEMM_WGN>;
   constexpr int smem = 2 * 2 * 256 * BK * 2;
   static bool attr_set = false;
   if (!attr_set) {
@@ -427,41 +294,20 @@ static int launch_bf16_dtl(const void* A, const void* B, void* C, const void* bi
       return PTDP_E_HIP;
     attr_set = true;
   }
-  const int tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(512), smem, st, (const bf16_t*)A, (const bf16_t*)B, C,
-                     (const bf16_t*)bias, M, N, K, accumulate);
-  return PTDP_OK;
-}
-
-template <int BM, int BN, int WM, int WN, bool TA, bool TB, bool OUT_F32>
-static int launch_bf16_cfg(const void* A, const void* B, void* C, const void* bias, int M, int N, int K, int accumulate,
-                           hipStream_t st) {
-  auto kern = gemm_bf16_kernel<BM, BN, WM, WN, TA, TB, OUT_F32>;
-  constexpr int smem = 2 * (BM + BN) * BK * 2;
-  static bool attr_set = false;  // per instantiation; benign race (idempotent call)
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
-        hipSuccess)
-      return PTDP_E_HIP;
-    attr_set = true;
-  }
-  const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), smem, st, (const bf16_t*)A, (const bf16_t*)B, C,
-                     (const bf16_t*)bias, M, N, K, accumulate);
+  const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+  const int tiles = 8 * tiles_m * ((tiles_n + 7) / 8);  // 8 XCD queues of equal length; surplus blocks exit at once
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(PTDP_GEMM_WGM * PTDP_GEMM_WGN * 64), smem, st, (const bf16_t*)A,
+                     (const bf16_t*)B, C, (const bf16_t*)bias, M, N, K, accumulate);
   return PTDP_OK;
 }
 
 template <bool TA, bool TB>
 static int launch_bf16_mode(const void* A, const void* B, void* C, const void* bias, int M, int N, int K, int out_f32,
                             int accumulate, hipStream_t st) {
-  // the direct-to-LDS kernel addresses each operand through a 31-bit byte offset
-  const bool small = (size_t)M * K * 2 < 0x7fffffffull && (size_t)N * K * 2 < 0x7fffffffull && K > 0;
-  if (small) {
-    if (out_f32) return launch_bf16_dtl<TA, TB, true>(A, B, C, bias, M, N, K, accumulate, st);
-    return launch_bf16_dtl<TA, TB, false>(A, B, C, bias, M, N, K, accumulate, st);
-  }
-  if (out_f32) return launch_bf16_cfg<256, 256, 128, 128, TA, TB, true>(A, B, C, bias, M, N, K, accumulate, st);
-  return launch_bf16_cfg<256, 256, 128, 128, TA, TB, false>(A, B, C, bias, M, N, K, accumulate, st);
+  // the kernel addresses each operand through a 31-bit byte offset from the block's first row
+  if ((size_t)M * K * 2 >= 0x7fffffffull || (size_t)N * K * 2 >= 0x7fffffffull) return PTDP_E_UNSUPPORTED;
+  if (out_f32) return launch_bf16_dtl<TA, TB, true>(A, B, C, bias, M, N, K, accumulate, st);
+  return launch_bf16_dtl<TA, TB, false>(A, B, C, bias, M, N, K, accumulate, st);
 }
 
 int launch_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N, int K,
