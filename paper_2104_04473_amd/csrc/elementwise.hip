@@ -70,90 +70,97 @@ __global__ void layernorm_fwd_kernel(const T* __restrict__ x, const T* __restric
   }
 }
 
-// LayerNorm backward.  Block handles `rpb` consecutive rows; per row
+// LayerNorm backward, input gradient.  One block per row, the row of du and x lives in registers:
 //   xhat = (x-mu)*rstd, dxhat = du*gain, dx = resid + rstd*(dxhat - mean(dxhat) - xhat*mean(dxhat*xhat)).
-// Per-thread column partials of sum(du*xhat) and sum(du) go to part[blockIdx][2*width].
 template <typename T, int VPT>
-__global__ void layernorm_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const T* __restrict__ gain,
-                                     const float* __restrict__ mu, const float* __restrict__ rstd,
-                                     const T* resid, T* dx, float* __restrict__ part, int rows, int width,
-                                     int rpb) {
+__global__ void layernorm_bwd_dx_kernel(const T* __restrict__ du, const T* __restrict__ x, const T* __restrict__ gain,
+                                        const float* __restrict__ mu, const float* __restrict__ rstd, const T* resid,
+                                        T* dx, int width) {
   constexpr int N = Vec16<T>::N;
   __shared__ float red[16];
   const int nvec = width / N;
-  float gf[VPT][N], acc_g[VPT][N], acc_b[VPT][N];
+  const size_t base = (size_t)blockIdx.x * width;
+  const float m = mu[blockIdx.x], rs = rstd[blockIdx.x];
+  float dxh[VPT][N], xh[VPT][N];
+  float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int i = 0; i < VPT; ++i) {
     const int c = threadIdx.x + i * blockDim.x;
-#pragma unroll
-    for (int j = 0; j < N; ++j) acc_g[i][j] = acc_b[i][j] = 0.f;
     if (c < nvec) {
-      Vec16<T> g;
+      Vec16<T> a, b, g;
+      float gf[N];
+      a.load(du + base + (size_t)c * N);
+      b.load(x + base + (size_t)c * N);
       g.load(gain + (size_t)c * N);
-      g.unpack(gf[i]);
-    }
-  }
-  const int r0 = blockIdx.x * rpb;
-  const int r1 = min(rows, r0 + rpb);
-  for (int row = r0; row < r1; ++row) {
-    const size_t base = (size_t)row * width;
-    const float m = mu[row], rs = rstd[row];
-    float dv[VPT][N], xh[VPT][N];
-    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      const int c = threadIdx.x + i * blockDim.x;
-      if (c < nvec) {
-        Vec16<T> a, b;
-        a.load(du + base + (size_t)c * N);
-        b.load(x + base + (size_t)c * N);
-        a.unpack(dv[i]);
-        b.unpack(xh[i]);
-#pragma unroll
-        for (int j = 0; j < N; ++j) {
-          xh[i][j] = (xh[i][j] - m) * rs;
-          acc_g[i][j] += dv[i][j] * xh[i][j];
-          acc_b[i][j] += dv[i][j];
-          const float dxh = dv[i][j] * gf[i][j];
-          s1 += dxh;
-          s2 += dxh * xh[i][j];
-        }
-      }
-    }
-    const float c1 = block_sum(s1, red) / (float)width;
-    const float c2 = block_sum(s2, red) / (float)width;
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      const int c = threadIdx.x + i * blockDim.x;
-      if (c < nvec) {
-        float of[N];
-        if (resid) {
-          Vec16<T> rr;
-          rr.load(resid + base + (size_t)c * N);
-          rr.unpack(of);
-        } else {
-#pragma unroll
-          for (int j = 0; j < N; ++j) of[j] = 0.f;
-        }
-#pragma unroll
-        for (int j = 0; j < N; ++j) of[j] += rs * (dv[i][j] * gf[i][j] - c1 - xh[i][j] * c2);
-        Vec16<T> o;
-        o.pack(of);
-        o.store(dx + base + (size_t)c * N);
-      }
-    }
-  }
-  float* prow = part + (size_t)blockIdx.x * 2 * width;
-#pragma unroll
-  for (int i = 0; i < VPT; ++i) {
-    const int c = threadIdx.x + i * blockDim.x;
-    if (c < nvec) {
+      a.unpack(dxh[i]);
+      b.unpack(xh[i]);
+      g.unpack(gf);
 #pragma unroll
       for (int j = 0; j < N; ++j) {
-        prow[(size_t)c * N + j] = acc_g[i][j];
-        prow[(size_t)width + (size_t)c * N + j] = acc_b[i][j];
+        xh[i][j] = (xh[i][j] - m) * rs;
+        dxh[i][j] *= gf[j];
+        s1 += dxh[i][j];
+        s2 += dxh[i][j] * xh[i][j];
       }
     }
+  }
+  const float c1 = block_sum(s1, red) / (float)width;
+  const float c2 = block_sum(s2, red) / (float)width;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int c = threadIdx.x + i * blockDim.x;
+    if (c < nvec) {
+      float of[N];
+      if (resid) {
+        Vec16<T> rr;
+        rr.load(resid + base + (size_t)c * N);
+        rr.unpack(of);
+      } else {
+#pragma unroll
+        for (int j = 0; j < N; ++j) of[j] = 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < N; ++j) of[j] += rs * (dxh[i][j] - c1 - xh[i][j] * c2);
+      Vec16<T> o;
+      o.pack(of);
+      o.store(dx + base + (size_t)c * N);
+    }
+  }
+}
+
+// LayerNorm backward, parameter gradients: part[blockIdx.y][c] = sum_r du*xhat, part[..][width + c] = sum_r du
+// over the block's kColRows rows; thread owns one 16-byte column group.
+template <typename T>
+__global__ void layernorm_bwd_param_kernel(const T* __restrict__ du, const T* __restrict__ x,
+                                           const float* __restrict__ mu, const float* __restrict__ rstd,
+                                           float* __restrict__ part, int rows, int width) {
+  constexpr int N = Vec16<T>::N;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= width / N) return;
+  float ag[N], ab[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) ag[j] = ab[j] = 0.f;
+  const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
+  for (int r = r0; r < r1; ++r) {
+    const size_t off = (size_t)r * width + (size_t)c * N;
+    const float m = mu[r], rs = rstd[r];
+    Vec16<T> a, b;
+    float af[N], xf[N];
+    a.load(du + off);
+    b.load(x + off);
+    a.unpack(af);
+    b.unpack(xf);
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      ag[j] += af[j] * ((xf[j] - m) * rs);
+      ab[j] += af[j];
+    }
+  }
+  float* prow = part + (size_t)blockIdx.y * 2 * width;
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    prow[(size_t)c * N + j] = ag[j];
+    prow[(size_t)width + (size_t)c * N + j] = ab[j];
   }
 }
 
@@ -354,22 +361,10 @@ static inline int ln_threads(int nvec, int* vpt) {
   return threads;
 }
 
-static inline int ln_rows_per_block(int rows) {
-  int rpb = (rows + 255) / 256;
-  if (rpb < 1) rpb = 1;
-  if (rpb > 16) rpb = 16;
-  return rpb;
-}
-
 size_t colsum_scratch_bytes(int rows, int width) {
-  // enough for either producer: LayerNorm backward writes ceil(rows / rpb) parts (its `width` is twice
-  // the row width), the row-tile producers write ceil(rows / kColRows) parts.
+  // one row of `width` floats per tile of kColRows rows (LayerNorm backward passes twice its row width)
   if (rows <= 0 || width <= 0) return 0;
-  const int rpb = ln_rows_per_block(rows);
-  size_t parts = (size_t)((rows + rpb - 1) / rpb);
-  const size_t tiles = (size_t)((rows + kColRows - 1) / kColRows);
-  if (tiles > parts) parts = tiles;
-  return parts * (size_t)width * sizeof(float);
+  return (size_t)((rows + kColRows - 1) / kColRows) * (size_t)width * sizeof(float);
 }
 
 template <typename T>
@@ -417,15 +412,21 @@ static int ln_bwd_t(const void* du, const void* x, const void* gain, const float
   int vpt;
   const int threads = ln_threads(width / N, &vpt);
   if (vpt > 8) return PTDP_E_UNSUPPORTED;
-  const int rpb = ln_rows_per_block(rows);
-  const int nblk = (rows + rpb - 1) / rpb;
   float* part = (float*)scratch;
+  const dim3 pgrid((width / N + 255) / 256, (rows + kColRows - 1) / kColRows);
+  {
+    // the parameter gradients read du before dx may overwrite it (dx may alias du)
+    Launch L(PTDP_K_LN_BWD, (double)rows * width * sizeof(T) * 2, st);
+    hipLaunchKernelGGL((layernorm_bwd_param_kernel<T>), pgrid, dim3(256), 0, st, (const T*)du, (const T*)x, mu, rstd,
+                       part, rows, width);
+    if (L.status() != PTDP_OK) return L.status();
+  }
   {
     const double bytes = (double)rows * width * sizeof(T) * (resid ? 4 : 3);
     Launch L(PTDP_K_LN_BWD, bytes, st);
-#define PTDP_LN_BWD(V)                                                                                          \
-  hipLaunchKernelGGL((layernorm_bwd_kernel<T, V>), dim3(nblk), dim3(threads), 0, st, (const T*)du, (const T*)x,  \
-                     (const T*)gain, mu, rstd, (const T*)resid, (T*)dx, part, rows, width, rpb)
+#define PTDP_LN_BWD(V)                                                                                           \
+  hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), dim3(rows), dim3(threads), 0, st, (const T*)du, (const T*)x, \
+                     (const T*)gain, mu, rstd, (const T*)resid, (T*)dx, width)
     switch (vpt) {
       case 1: PTDP_LN_BWD(1); break;
       case 2: PTDP_LN_BWD(2); break;
@@ -435,7 +436,7 @@ static int ln_bwd_t(const void* du, const void* x, const void* gain, const float
 #undef PTDP_LN_BWD
     if (L.status() != PTDP_OK) return L.status();
   }
-  return colsum_finish(part, nblk, 2 * width, dgain, dbias, width, st);
+  return colsum_finish(part, pgrid.y, 2 * width, dgain, dbias, width, st);
 }
 
 int launch_layernorm_bwd(int dtype, const void* du, const void* x, const void* gain, const float* mu,
