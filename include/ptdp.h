@@ -263,10 +263,14 @@ int ptdp_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t seed, uint32_t
  *   mode PTDP_GEMM_TN: A [K,M] row-major, B [K,N] row-major      (weight grad: dW = X^T dY)
  * A, B in `dtype`.  out_f32 = 0: C in `dtype`, overwritten; out_f32 = 1: C fp32,
  * accumulated (+=) when accumulate != 0.  bias [N] in `dtype` or NULL.  bf16
- * needs M, N, K multiples of 8 (no other shape restriction). */
+ * needs M, N, K multiples of 8 and operands below 2 GiB.  workspace (dev, may
+ * be NULL): fp32 scratch of up to M*N*4 bytes; with it, a tile count that does
+ * not fill the compute units evenly is finished by splitting the remaining
+ * tiles along k (their partial sums are added with fp32 atomics, so the last
+ * bits of those outputs may differ between runs). */
 enum { PTDP_GEMM_NN = 0, PTDP_GEMM_NT = 1, PTDP_GEMM_TN = 2 };
 int ptdp_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N,
-              int K, int out_f32, int accumulate, void* stream);
+              int K, int out_f32, int accumulate, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Fused causal attention over qkv [s, b, 3hp] (scale 1/sqrt(dh), implicit
  * causal mask, softmax, times V; section 4.2's scale+mask+softmax fusion

@@ -119,7 +119,7 @@ static StashLayout stash_layout(const ptdp_layer_cfg* c) {
 }
 
 // workspace fields
-enum { WS_H1 = 0, WS_H2, WS_X1, WS_CHAIN, WS_BIG, WS_CTX, WS_QKV, WS_DELTA, WS_COLSUM, WS_N };
+enum { WS_H1 = 0, WS_H2, WS_X1, WS_CHAIN, WS_BIG, WS_CTX, WS_QKV, WS_DELTA, WS_COLSUM, WS_SPLITK, WS_N };
 struct WsLayout {
   size_t off[WS_N];
   size_t total;
@@ -137,6 +137,10 @@ static WsLayout ws_layout(const ptdp_layer_cfg* c) {
   if (c2 > cs) cs = c2;
   if (c3 > cs) cs = c3;
   sz[WS_COLSUM] = cs;
+  // fp32 image of the widest bf16 GEMM output, for output tiles that are split along k
+  int64_t widest = d.fp > d.h ? d.fp : d.h;
+  if (3 * d.hp > widest) widest = 3 * d.hp;
+  sz[WS_SPLITK] = c->dtype == PTDP_BF16 ? (size_t)d.T * widest * sizeof(float) : 0;
   WsLayout L;
   size_t o = 0;
   for (int i = 0; i < WS_N; ++i) {
@@ -145,6 +149,10 @@ static WsLayout ws_layout(const ptdp_layer_cfg* c) {
   }
   L.total = o;
   return L;
+}
+
+static inline size_t ws_field_bytes(const WsLayout& L, int f) {
+  return (f + 1 < WS_N ? L.off[f + 1] : L.total) - L.off[f];
 }
 
 }  // namespace ptdp
@@ -273,23 +281,25 @@ int ptdp_layer_forward(ptdp_chunk* ch, int layer, int64_t microbatch, const void
   const int T = (int)d.T, h = (int)d.h, hp = (int)d.hp, fp = (int)d.fp;
   const uint32_t gl = (uint32_t)(ch->first_layer + layer);
   void* o = W + ch->wl.off[WS_H1];
+  void* sk = W + ch->wl.off[WS_SPLITK];
+  const size_t skb = ws_field_bytes(ch->wl, WS_SPLITK);
   void* x_copy = (x == sf(PTDP_STASH_X)) ? nullptr : sf(PTDP_STASH_X);
 
   PTDP_TRY(launch_layernorm_fwd(c.dtype, x, P.ln1_g, P.ln1_b, sf(PTDP_STASH_U), (float*)sf(PTDP_STASH_MU1),
                                 (float*)sf(PTDP_STASH_RSTD1), x_copy, T, h, c.ln_eps, st));
   PTDP_TRY(launch_gemm(c.dtype, PTDP_GEMM_NN, sf(PTDP_STASH_U), P.w_qkv, sf(PTDP_STASH_QKV), P.b_qkv, T, 3 * hp, h, 0,
-                       0, st));
+                       0, sk, skb, st));
   PTDP_TRY(launch_attn_fwd(c.dtype, sf(PTDP_STASH_QKV), sf(PTDP_STASH_CTX), (float*)sf(PTDP_STASH_LSE), c.s, c.b,
                            (int)d.al, (int)d.dh, st));
-  PTDP_TRY(launch_gemm(c.dtype, PTDP_GEMM_NN, sf(PTDP_STASH_CTX), P.w_o, o, nullptr, T, h, hp, 0, 0, st));
+  PTDP_TRY(launch_gemm(c.dtype, PTDP_GEMM_NN, sf(PTDP_STASH_CTX), P.w_o, o, nullptr, T, h, hp, 0, 0, sk, skb, st));
   PTDP_TRY(launch_bda_fwd(c.dtype, o, P.b_o, x, sf(PTDP_STASH_X1), T, h, c.p_hidden,
                           dropout_key(c.seed, gl, 0, (uint64_t)microbatch), st));
   PTDP_TRY(launch_layernorm_fwd(c.dtype, sf(PTDP_STASH_X1), P.ln2_g, P.ln2_b, sf(PTDP_STASH_U2),
                                 (float*)sf(PTDP_STASH_MU2), (float*)sf(PTDP_STASH_RSTD2), nullptr, T, h, c.ln_eps,
                                 st));
-  PTDP_TRY(launch_gemm(c.dtype, PTDP_GEMM_NN, sf(PTDP_STASH_U2), P.w_1, sf(PTDP_STASH_Z), nullptr, T, fp, h, 0, 0, st));
+  PTDP_TRY(launch_gemm(c.dtype, PTDP_GEMM_NN, sf(PTDP_STASH_U2), P.w_1, sf(PTDP_STASH_Z), nullptr, T, fp, h, 0, 0, sk, skb, st));
   PTDP_TRY(launch_bias_gelu_fwd(c.dtype, c.gelu_mode, sf(PTDP_STASH_Z), P.b_1, sf(PTDP_STASH_G), T, fp, st));
-  PTDP_TRY(launch_gemm(c.dtype, PTDP_GEMM_NN, sf(PTDP_STASH_G), P.w_2, o, nullptr, T, h, fp, 0, 0, st));
+  PTDP_TRY(launch_gemm(c.dtype, PTDP_GEMM_NN, sf(PTDP_STASH_G), P.w_2, o, nullptr, T, h, fp, 0, 0, sk, skb, st));
   PTDP_TRY(launch_bda_fwd(c.dtype, o, P.b_2, sf(PTDP_STASH_X1), y, T, h, c.p_hidden,
                           dropout_key(c.seed, gl, 1, (uint64_t)microbatch), st));
   return PTDP_OK;
@@ -313,27 +323,29 @@ int ptdp_layer_backward(ptdp_chunk* ch, int layer, int64_t microbatch, const voi
   const uint32_t gl = (uint32_t)(ch->first_layer + layer);
   const int dt = c.dtype;
   void* cs = wf(WS_COLSUM);
+  void* sk = wf(WS_SPLITK);
+  const size_t skb = ws_field_bytes(ch->wl, WS_SPLITK);
 
   // MLP block
   PTDP_TRY(launch_bda_bwd(dt, dy, wf(WS_H1), G.b_2, cs, T, h, c.p_hidden,
                           dropout_key(c.seed, gl, 1, (uint64_t)microbatch), st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_2, wf(WS_BIG), nullptr, T, fp, h, 0, 0, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_G), wf(WS_H1), G.w_2, nullptr, fp, h, T, 1, 1, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_2, wf(WS_BIG), nullptr, T, fp, h, 0, 0, sk, skb, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_G), wf(WS_H1), G.w_2, nullptr, fp, h, T, 1, 1, sk, skb, st));
   PTDP_TRY(launch_bias_gelu_bwd(dt, c.gelu_mode, wf(WS_BIG), sf(PTDP_STASH_Z), P.b_1, wf(WS_BIG), G.b_1, cs, T, fp, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_BIG), P.w_1, wf(WS_H2), nullptr, T, h, fp, 0, 0, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_U2), wf(WS_BIG), G.w_1, nullptr, h, fp, T, 1, 1, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_BIG), P.w_1, wf(WS_H2), nullptr, T, h, fp, 0, 0, sk, skb, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_U2), wf(WS_BIG), G.w_1, nullptr, h, fp, T, 1, 1, sk, skb, st));
   PTDP_TRY(launch_layernorm_bwd(dt, wf(WS_H2), sf(PTDP_STASH_X1), P.ln2_g, (const float*)sf(PTDP_STASH_MU2),
                                 (const float*)sf(PTDP_STASH_RSTD2), dy, wf(WS_X1), G.ln2_g, G.ln2_b, cs, T, h, st));
   // attention block
   PTDP_TRY(launch_bda_bwd(dt, wf(WS_X1), wf(WS_H1), G.b_o, cs, T, h, c.p_hidden,
                           dropout_key(c.seed, gl, 0, (uint64_t)microbatch), st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_o, wf(WS_CTX), nullptr, T, hp, h, 0, 0, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_CTX), wf(WS_H1), G.w_o, nullptr, hp, h, T, 1, 1, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_o, wf(WS_CTX), nullptr, T, hp, h, 0, 0, sk, skb, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_CTX), wf(WS_H1), G.w_o, nullptr, hp, h, T, 1, 1, sk, skb, st));
   PTDP_TRY(launch_attn_bwd(dt, sf(PTDP_STASH_QKV), sf(PTDP_STASH_CTX), (const float*)sf(PTDP_STASH_LSE), wf(WS_CTX),
                            wf(WS_QKV), (float*)wf(WS_DELTA), c.s, c.b, (int)d.al, (int)d.dh, st));
   PTDP_TRY(launch_colsum(dt, wf(WS_QKV), G.b_qkv, cs, T, 3 * hp, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_QKV), P.w_qkv, wf(WS_H2), nullptr, T, h, 3 * hp, 0, 0, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_U), wf(WS_QKV), G.w_qkv, nullptr, h, 3 * hp, T, 1, 1, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_QKV), P.w_qkv, wf(WS_H2), nullptr, T, h, 3 * hp, 0, 0, sk, skb, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_U), wf(WS_QKV), G.w_qkv, nullptr, h, 3 * hp, T, 1, 1, sk, skb, st));
   PTDP_TRY(launch_layernorm_bwd(dt, wf(WS_H2), sf(PTDP_STASH_X), P.ln1_g, (const float*)sf(PTDP_STASH_MU1),
                                 (const float*)sf(PTDP_STASH_RSTD1), wf(WS_X1), dx, G.ln1_g, G.ln1_b, cs, T, h, st));
   return PTDP_OK;
@@ -551,14 +563,16 @@ int ptdp_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t seed, uint32_t
 }
 
 int ptdp_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N, int K,
-              int out_f32, int accumulate, void* stream) {
+              int out_f32, int accumulate, void* workspace, size_t workspace_bytes, void* stream) {
   PTDP_TRY(check_dtype(dtype));
   if (mode != PTDP_GEMM_NN && mode != PTDP_GEMM_NT && mode != PTDP_GEMM_TN) return PTDP_E_INVALID_ARG;
   if (M < 0 || N < 0 || K < 0) return PTDP_E_INVALID_ARG;
   if (dtype == PTDP_BF16 && (M % 8 || N % 8 || K % 8)) return PTDP_E_INVALID_ARG;
   if (dtype == PTDP_BF16 && accumulate && !out_f32) return PTDP_E_INVALID_ARG;
   if (!A || !B || !C) return PTDP_E_NULL_PTR;
-  return launch_gemm(dtype, mode, A, B, C, bias, M, N, K, out_f32, accumulate, (hipStream_t)stream);
+  if (!workspace) workspace_bytes = 0;
+  return launch_gemm(dtype, mode, A, B, C, bias, M, N, K, out_f32, accumulate, workspace, workspace_bytes,
+                     (hipStream_t)stream);
 }
 
 int ptdp_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, int b, int heads, int dh, void* stream) {

@@ -159,58 +159,49 @@ __device__ __forceinline__ bf16x8_t read_frag(const char* tile, int row_base, in
 // s_waitcnt vmcnt(0) only (gfx9 encoding: lgkmcnt and expcnt fields left at their maxima)
 __device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0f70); }
 
-// WGM x WGN waves, each (256/WGM) x (256/WGN); two LDS stages; the loads of k-tile kt+1 are issued
-// while k-tile kt is multiplied.  Fragments are double-buffered in registers: the reads of k16 step
-// kk+1 (or of the next tile's step 0, after the barrier) are issued before the MFMAs of step kk.
-template <bool TA, bool TB, bool OUT_F32, int WGM, int WGN>
-__global__ void __launch_bounds__(WGM * WGN * 64)
-gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, void* Cv,
-                     const bf16_t* __restrict__ bias, int M, int N, int K, int accumulate) {
-  constexpr int BM = 256, BN = 256, NW = WGM * WGN, WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
-  constexpr int TILE_BYTES = 256 * BK * 2, STAGE_BYTES = 2 * TILE_BYTES, NKK = BK / 16;
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
+// Operands of one GEMM call as the kernels see them.  N is the number of columns this launch covers;
+// ldb / ldc are the row lengths of the full B (k-slow form) and C, so that a launch may cover a column
+// range of a larger problem.  a_end / b_end: one past the last byte of the operands (descriptor bounds).
+struct GemmArgs {
+  const bf16_t* A;
+  const bf16_t* B;
+  const bf16_t* bias;
+  const char* a_end;
+  const char* b_end;
+  int M, N, K;
+  size_t lda, ldb, ldc;
+};
 
-  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Each XCD owns the column
-  // tiles x, x+8, ... and works through them in groups of up to 8 row tiles, so that the
-  // workgroups resident on one XCD share 8 A panels and 4 B panels through that L2.
-  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int nx = (tiles_n + 7) / 8;                 // column tiles per XCD (some may be past the end)
-  const int per_group = 8 * nx;                     // blocks of one full group of 8 row tiles
-  const int grp = local / per_group, in_grp = local % per_group;
-  const int gm = min(8, tiles_m - grp * 8);         // row tiles in this group
-  const int tile_m = grp * 8 + in_grp % gm, tile_n = (in_grp / gm) * 8 + xcd;
-  if (tile_n >= tiles_n) return;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const size_t lda = TA ? (size_t)M : (size_t)K;
-  const size_t ldb = TB ? (size_t)N : (size_t)K;
+constexpr int kBM = 256, kBN = 256;
+constexpr int kTileBytes = 256 * BK * 2, kStageBytes = 2 * kTileBytes;
+
+// acc += A[m0.., k] B[n0.., k] over k-tiles kt0 .. kt1-1.  WGM x WGN waves, each (256/WGM) x (256/WGN);
+// two LDS stages; the loads of k-tile kt+1 are issued while k-tile kt is multiplied.  Fragments are
+// double-buffered in registers: the reads of k16 step kk+1 (or of the next tile's step 0, after the
+// barrier) are issued before the MFMAs of step kk.
+template <bool TA, bool TB, int WGM, int WGN>
+__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kBN / WGN / 32], const GemmArgs& g,
+                                              int m0, int n0, int kt0, int kt1, char* smem) {
+  constexpr int NW = WGM * WGN, WM = kBM / WGM, WN = kBN / WGN, TM = WM / 32, TN = WN / 32, NKK = BK / 16;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
-
   // buffer descriptors start at the block's first row so that lane offsets stay small
-  const bf16_t* a_base = TA ? A + m0 : A + (size_t)m0 * lda;
-  const bf16_t* b_base = TB ? B + n0 : B + (size_t)n0 * ldb;
-  const size_t a_total = (size_t)M * K * 2, b_total = (size_t)N * K * 2;
-  const size_t a_left = a_total - (size_t)(a_base - A) * 2, b_left = b_total - (size_t)(b_base - B) * 2;
+  const bf16_t* a_base = TA ? g.A + m0 : g.A + (size_t)m0 * g.lda;
+  const bf16_t* b_base = TB ? g.B + n0 : g.B + (size_t)n0 * g.ldb;
+  const size_t a_left = (size_t)(g.a_end - reinterpret_cast<const char*>(a_base));
+  const size_t b_left = (size_t)(g.b_end - reinterpret_cast<const char*>(b_base));
   const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, (uint32_t)(a_left < 0x7fffffffu ? a_left : 0x7fffffffu));
   const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, (uint32_t)(b_left < 0x7fffffffu ? b_left : 0x7fffffffu));
+  const int kend = min(g.K, kt1 * BK);  // k-tiles from kt1 on read as zeros
 
   TileLoad<TA, NW> la;
   TileLoad<TB, NW> lb;
-  la.init(lda, M - m0, wave, lane);
-  lb.init(ldb, N - n0, wave, lane);
+  la.init(g.lda, g.M - m0, wave, lane);
+  lb.init(g.ldb, g.N - n0, wave, lane);
 
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  const int nk = (K + BK - 1) / BK;
-  la.issue(ra, smem, wave, lane, 0, K);
-  lb.issue(rb, smem + TILE_BYTES, wave, lane, 0, K);
+  __syncthreads();  // LDS may still be read by a slower wave of the previous tile
+  la.issue(ra, smem, wave, lane, kt0, kend);
+  lb.issue(rb, smem + kTileBytes, wave, lane, kt0, kend);
   wait_vmcnt0();
   __syncthreads();
 
@@ -218,14 +209,14 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
 #pragma unroll
   for (int i = 0; i < TM; ++i) af[0][i] = read_frag<TA>(smem, wm0 + i * 32, 0, lane);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) bfr[0][j] = read_frag<TB>(smem + TILE_BYTES, wn0 + j * 32, 0, lane);
+  for (int j = 0; j < TN; ++j) bfr[0][j] = read_frag<TB>(smem + kTileBytes, wn0 + j * 32, 0, lane);
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const char* cur = smem + (kt & 1) * STAGE_BYTES;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE_BYTES;
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const char* cur = smem + ((kt - kt0) & 1) * kStageBytes;
+    char* nxt = smem + ((kt - kt0 + 1) & 1) * kStageBytes;
     // stage nxt was last read before the barrier that ended the previous iteration's reads
-    la.issue(ra, nxt, wave, lane, kt + 1, K);
-    lb.issue(rb, nxt + TILE_BYTES, wave, lane, kt + 1, K);
+    la.issue(ra, nxt, wave, lane, kt + 1, kend);
+    lb.issue(rb, nxt + kTileBytes, wave, lane, kt + 1, kend);
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk) {
       const int c = kk & 1, n = c ^ 1;
@@ -233,7 +224,7 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
 #pragma unroll
         for (int i = 0; i < TM; ++i) af[n][i] = read_frag<TA>(cur, wm0 + i * 32, kk + 1, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[n][j] = read_frag<TB>(cur + TILE_BYTES, wn0 + j * 32, kk + 1, lane);
+        for (int j = 0; j < TN; ++j) bfr[n][j] = read_frag<TB>(cur + kTileBytes, wn0 + j * 32, kk + 1, lane);
       } else {
         // every fragment of `cur` is in registers: the next tile may be consumed, `cur` may be refilled
         wait_vmcnt0();
@@ -241,7 +232,7 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
 #pragma unroll
         for (int i = 0; i < TM; ++i) af[n][i] = read_frag<TA>(nxt, wm0 + i * 32, 0, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[n][j] = read_frag<TB>(nxt + TILE_BYTES, wn0 + j * 32, 0, lane);
+        for (int j = 0; j < TN; ++j) bfr[n][j] = read_frag<TB>(nxt + kTileBytes, wn0 + j * 32, 0, lane);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -250,7 +241,16 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bfr[c][j], acc[i][j], 0, 0, 0);
     }
   }
+}
 
+// Output forms.  32x32 accumulator layout: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane/32) + r%4.
+enum { OUT_BF16 = 0, OUT_F32_STORE = 1, OUT_F32_ADD = 2 };
+template <int OUT, int WGM, int WGN>
+__device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[kBM / WGM / 32][kBN / WGN / 32], void* Cv, size_t ldc,
+                                              const bf16_t* bias, int M, int N, int m0, int n0) {
+  constexpr int WM = kBM / WGM, WN = kBN / WGN, TM = WM / 32, TN = WN / 32;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int n = n0 + wn0 + j * 32 + (lane & 31);
@@ -263,55 +263,199 @@ gemm_bf16_dtl_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
         const int m = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (m >= M) continue;
         const float val = acc[i][j][r] + bv;
-        if (OUT_F32) {
-          float* c = reinterpret_cast<float*>(Cv) + (size_t)m * N + n;
-          // every element is owned by one lane, so the L2-side add is as deterministic as a
-          // read-modify-write here would be, without the round trip
-          if (accumulate) unsafeAtomicAdd(c, val);
-          else *c = val;
+        if (OUT == OUT_BF16) {
+          reinterpret_cast<bf16_t*>(Cv)[(size_t)m * ldc + n] = f32_to_bf16(val);
+        } else if (OUT == OUT_F32_STORE) {
+          reinterpret_cast<float*>(Cv)[(size_t)m * ldc + n] = val;
         } else {
-          reinterpret_cast<bf16_t*>(Cv)[(size_t)m * N + n] = f32_to_bf16(val);
+          // the add happens in L2; within one launch every element is touched by a fixed set of
+          // workgroups, so only the order of a few fp32 additions can vary
+          unsafeAtomicAdd(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n, val);
         }
       }
     }
   }
 }
 
-#ifndef PTDP_GEMM_WGM
-#define PTDP_GEMM_WGM 2
-#define PTDP_GEMM_WGN 4
-#endif
+template <int TM, int TN> __device__ __forceinline__ void zero_acc(f32x16_t (&acc)[TM][TN]) {
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+}
 
-template <bool TA, bool TB, bool OUT_F32>
-static int launch_bf16_dtl(const void* A, const void* B, void* C, const void* bias, int M, int N, int K,
-                           int accumulate, hipStream_t st) {
-  auto kern = gemm_bf16_dtl_kernel<TA, TB, OUT_F32, PTDP_GEMM_WGM, PTDP_GEMM_WGN>;
-  constexpr int smem = 2 * 2 * 256 * BK * 2;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem) !=
-        hipSuccess)
-      return PTDP_E_HIP;
-    attr_set = true;
+// One workgroup per output tile ("data-parallel" form).
+template <bool TA, bool TB, int OUT, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64)
+gemm_bf16_dp_kernel(GemmArgs g, void* Cv) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Each XCD owns the column
+  // tiles x, x+8, ... and works through them in groups of up to 8 row tiles, so that the
+  // workgroups resident on one XCD share 8 A panels and 4 B panels through that L2.
+  const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int nx = (tiles_n + 7) / 8;                 // column tiles per XCD (some may be past the end)
+  const int per_group = 8 * nx;                     // blocks of one full group of 8 row tiles
+  const int grp = local / per_group, in_grp = local % per_group;
+  const int gm = min(8, tiles_m - grp * 8);         // row tiles in this group
+  const int tile_m = grp * 8 + in_grp % gm, tile_n = (in_grp / gm) * 8 + xcd;
+  if (tile_n >= tiles_n) return;
+  f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
+  zero_acc(acc);
+  gemm_mainloop<TA, TB, WGM, WGN>(acc, g, tile_m * kBM, tile_n * kBN, 0, (g.K + BK - 1) / BK, smem);
+  gemm_epilogue<OUT, WGM, WGN>(acc, Cv, g.ldc, g.bias, g.M, g.N, tile_m * kBM, tile_n * kBN);
+}
+
+// "Stream-K" form for a tile count that does not fill the machine evenly: the (tile, k-tile) iteration
+// space is cut into gridDim.x equal contiguous ranges, one per workgroup; every range adds its partial
+// tile(s) into an fp32 matrix (zero, or a gradient accumulator) with L2 atomics.  No workgroup waits
+// for another one.
+template <bool TA, bool TB, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64)
+gemm_bf16_sk_kernel(GemmArgs g, float* Cacc, size_t ldacc) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
+  const int nk = (g.K + BK - 1) / BK;
+  const long long total = (long long)tiles_m * tiles_n * nk;
+  long long it = total * blockIdx.x / gridDim.x;
+  const long long it_end = total * (blockIdx.x + 1) / gridDim.x;
+  while (it < it_end) {
+    const int tile = (int)(it / nk), kt0 = (int)(it % nk);
+    const int kt1 = (int)min((long long)nk, kt0 + (it_end - it));
+    const int m0 = (tile % tiles_m) * kBM, n0 = (tile / tiles_m) * kBN;
+    f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
+    zero_acc(acc);
+    gemm_mainloop<TA, TB, WGM, WGN>(acc, g, m0, n0, kt0, kt1, smem);
+    gemm_epilogue<OUT_F32_ADD, WGM, WGN>(acc, Cacc, ldacc, nullptr, g.M, g.N, m0, n0);
+    it += kt1 - kt0;
   }
-  const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
-  const int tiles = 8 * tiles_m * ((tiles_n + 7) / 8);  // 8 XCD queues of equal length; surplus blocks exit at once
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(PTDP_GEMM_WGM * PTDP_GEMM_WGN * 64), smem, st, (const bf16_t*)A,
-                     (const bf16_t*)B, C, (const bf16_t*)bias, M, N, K, accumulate);
+}
+
+// ws[M, N] fp32 -> C[M, ldc] bf16 (+ bias); 4 elements per thread
+__global__ void gemm_sk_convert_kernel(const float* __restrict__ ws, bf16_t* __restrict__ C, const bf16_t* __restrict__ bias,
+                                       int M, int N, size_t ldc) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t nvec = (size_t)N / 4;
+  if (i >= (size_t)M * nvec) return;
+  const size_t m = i / nvec;
+  const int n = (int)(i % nvec) * 4;
+  const float4 v = *reinterpret_cast<const float4*>(ws + m * N + n);
+  float b[4] = {0.f, 0.f, 0.f, 0.f};
+  if (bias) {
+    const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
+    b[0] = __uint_as_float(bb.x << 16); b[1] = __uint_as_float(bb.x & 0xffff0000u);
+    b[2] = __uint_as_float(bb.y << 16); b[3] = __uint_as_float(bb.y & 0xffff0000u);
+  }
+  uint2 o;
+  o.x = pack_bf16x2(v.x + b[0], v.y + b[1]);
+  o.y = pack_bf16x2(v.z + b[2], v.w + b[3]);
+  *reinterpret_cast<uint2*>(C + m * ldc + n) = o;
+}
+
+__global__ void fill_zero_kernel(float4* p, size_t n4) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+constexpr int kWGM = 2, kWGN = 4, kGemmThreads = kWGM * kWGN * 64, kGemmSmem = 2 * kStageBytes;
+
+template <typename Kern> static int set_smem_once(Kern kern, bool* done) {
+  if (*done) return PTDP_OK;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmSmem) !=
+      hipSuccess)
+    return PTDP_E_HIP;
+  *done = true;
+  return PTDP_OK;
+}
+
+template <bool TA, bool TB, int OUT>
+static int launch_dp(const GemmArgs& g, void* C, hipStream_t st) {
+  auto kern = gemm_bf16_dp_kernel<TA, TB, OUT, kWGM, kWGN>;
+  static bool done = false;
+  if (set_smem_once(kern, &done) != PTDP_OK) return PTDP_E_HIP;
+  const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
+  const int blocks = 8 * tiles_m * ((tiles_n + 7) / 8);  // 8 XCD queues of equal length; surplus blocks exit at once
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, C);
   return PTDP_OK;
 }
 
 template <bool TA, bool TB>
+static int launch_sk(const GemmArgs& g, float* Cacc, size_t ldacc, int blocks, hipStream_t st) {
+  auto kern = gemm_bf16_sk_kernel<TA, TB, kWGM, kWGN>;
+  static bool done = false;
+  if (set_smem_once(kern, &done) != PTDP_OK) return PTDP_E_HIP;
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, Cacc, ldacc);
+  return PTDP_OK;
+}
+
+static int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+    n = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  }
+  return n;
+}
+
+// Splits the columns into a part whose tiles fill whole rounds of the machine (one workgroup per tile)
+// and a remainder that is spread evenly over all compute units in stream-K form.
+template <bool TA, bool TB>
 static int launch_bf16_mode(const void* A, const void* B, void* C, const void* bias, int M, int N, int K, int out_f32,
-                            int accumulate, hipStream_t st) {
+                            int accumulate, void* ws, size_t ws_bytes, hipStream_t st) {
   // the kernel addresses each operand through a 31-bit byte offset from the block's first row
   if ((size_t)M * K * 2 >= 0x7fffffffull || (size_t)N * K * 2 >= 0x7fffffffull) return PTDP_E_UNSUPPORTED;
-  if (out_f32) return launch_bf16_dtl<TA, TB, true>(A, B, C, bias, M, N, K, accumulate, st);
-  return launch_bf16_dtl<TA, TB, false>(A, B, C, bias, M, N, K, accumulate, st);
+  GemmArgs g;
+  g.A = (const bf16_t*)A;
+  g.B = (const bf16_t*)B;
+  g.bias = (const bf16_t*)bias;
+  g.a_end = (const char*)A + (size_t)M * K * 2;
+  g.b_end = (const char*)B + (size_t)N * K * 2;
+  g.M = M; g.N = N; g.K = K;
+  g.lda = TA ? (size_t)M : (size_t)K;
+  g.ldb = TB ? (size_t)N : (size_t)K;
+  g.ldc = (size_t)N;
+
+  const int ncu = compute_units();
+  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN, nk = (K + BK - 1) / BK;
+  const long long tiles = (long long)tiles_m * tiles_n;
+  const int rem = (int)(tiles % ncu);
+  const bool sk_out_ok = (out_f32 && accumulate && !bias) || (!out_f32 && ws != nullptr);
+  int dp_cols = tiles_n;
+  if (sk_out_ok && nk >= 64 && rem != 0 && rem * 100 < ncu * 88) {
+    dp_cols = (int)((tiles / ncu) * ncu / tiles_m);
+    if (!out_f32 && (size_t)M * (size_t)(N - dp_cols * kBN) * sizeof(float) > ws_bytes) dp_cols = tiles_n;
+  }
+  const int n_dp = dp_cols < tiles_n ? dp_cols * kBN : N;
+  if (n_dp > 0) {
+    GemmArgs d = g;
+    d.N = n_dp;
+    int rc;
+    if (!out_f32) rc = launch_dp<TA, TB, OUT_BF16>(d, C, st);
+    else if (accumulate) rc = launch_dp<TA, TB, OUT_F32_ADD>(d, C, st);
+    else rc = launch_dp<TA, TB, OUT_F32_STORE>(d, C, st);
+    if (rc != PTDP_OK) return rc;
+  }
+  if (n_dp < N) {
+    GemmArgs r = g;
+    r.N = N - n_dp;
+    r.B = TB ? g.B + n_dp : g.B + (size_t)n_dp * K;
+    if (out_f32) return launch_sk<TA, TB>(r, (float*)C + n_dp, (size_t)N, ncu, st);
+    const size_t n4 = (size_t)M * r.N / 4;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, st, (float4*)ws, n4);
+    const int rc = launch_sk<TA, TB>(r, (float*)ws, (size_t)r.N, ncu, st);
+    if (rc != PTDP_OK) return rc;
+    hipLaunchKernelGGL(gemm_sk_convert_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, (const float*)ws,
+                       (bf16_t*)C + n_dp, bias ? (const bf16_t*)bias + n_dp : nullptr, M, r.N, (size_t)N);
+  }
+  return PTDP_OK;
 }
 
 int launch_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N, int K,
-                int out_f32, int accumulate, hipStream_t st) {
+                int out_f32, int accumulate, void* ws, size_t ws_bytes, hipStream_t st) {
   if (M == 0 || N == 0) return PTDP_OK;
   const int fam = mode == PTDP_GEMM_NN ? PTDP_K_GEMM_NN : (mode == PTDP_GEMM_NT ? PTDP_K_GEMM_NT : PTDP_K_GEMM_TN);
   Launch L(fam, 2.0 * M * N * K, st);
@@ -325,9 +469,9 @@ int launch_gemm(int dtype, int mode, const void* A, const void* B, void* C, cons
   }
   int rc;
   switch (mode) {
-    case PTDP_GEMM_NN: rc = launch_bf16_mode<false, true>(A, B, C, bias, M, N, K, out_f32, accumulate, st); break;
-    case PTDP_GEMM_NT: rc = launch_bf16_mode<false, false>(A, B, C, bias, M, N, K, out_f32, accumulate, st); break;
-    default: rc = launch_bf16_mode<true, true>(A, B, C, bias, M, N, K, out_f32, accumulate, st); break;
+    case PTDP_GEMM_NN: rc = launch_bf16_mode<false, true>(A, B, C, bias, M, N, K, out_f32, accumulate, ws, ws_bytes, st); break;
+    case PTDP_GEMM_NT: rc = launch_bf16_mode<false, false>(A, B, C, bias, M, N, K, out_f32, accumulate, ws, ws_bytes, st); break;
+    default: rc = launch_bf16_mode<true, true>(A, B, C, bias, M, N, K, out_f32, accumulate, ws, ws_bytes, st); break;
   }
   if (rc != PTDP_OK) return rc;
   return L.status();

@@ -25,13 +25,48 @@ def test_gemm(dtype, mode, M, N, K):
     # storage-dtype output with bias
     c = torch.full((M, N), 9.0, dtype=tdt(dtype), device="cuda")
     B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), c.data_ptr(), bias.data_ptr(), M, N, K,
-                        1 if dtype == B.F32 else 0, 0, stream()), "gemm")
+                        1 if dtype == B.F32 else 0, 0, None, 0, stream()), "gemm")
     sync()
     assert_close(np64(c), want + np64(bias), dtype, "C")
     # fp32 accumulate (+=), twice
     acc = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")
     for _ in range(2):
-        B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), acc.data_ptr(), None, M, N, K, 1, 1, stream()), "gemm")
+        B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), acc.data_ptr(), None, M, N, K, 1, 1, None, 0, stream()), "gemm")
+    sync()
+    assert_close(np64(acc) - 0.5, 2 * want, dtype, "C +=")
+
+
+@pytest.mark.parametrize("mode", [B.GEMM_NN, B.GEMM_NT, B.GEMM_TN])
+@pytest.mark.parametrize("M,N,K", [(520, 776, 4168), (264, 4104, 4096), (2048, 1288, 4160), (2048, 10248, 4096)])
+def test_gemm_split_along_k(mode, M, N, K):
+    """Tile counts that do not fill the compute units: the remaining tiles are split along k through the
+    fp32 workspace (bf16 output) or straight into the fp32 accumulator."""
+    dtype = B.BF16
+    a = randn((M, K), dtype, 1)
+    b = randn((K, N), dtype, 2)
+    bias = randn((N,), dtype, 3)
+    want = np64(a) @ np64(b)
+    A = a.t().contiguous() if mode == B.GEMM_TN else a
+    Bm = b.t().contiguous() if mode == B.GEMM_NT else b
+    ws = torch.full((M * N,), 7.0, dtype=torch.float32, device="cuda")      # garbage on entry
+    c = torch.full((M, N), 9.0, dtype=torch.bfloat16, device="cuda")
+    B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), c.data_ptr(), bias.data_ptr(), M, N, K, 0, 0,
+                        ws.data_ptr(), ws.numel() * 4, stream()), "gemm")
+    sync()
+    assert_close(np64(c), want + np64(bias), dtype, "C")
+    # same result as the unsplit path up to bf16 rounding of an fp32 sum taken in another order
+    c2 = torch.empty_like(c)
+    B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), c2.data_ptr(), bias.data_ptr(), M, N, K, 0, 0,
+                        None, 0, stream()), "gemm")
+    sync()
+    assert_close(np64(c), np64(c2), dtype, "split vs unsplit", 0.2)
+    # too small a workspace falls back to the unsplit path
+    B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), c2.data_ptr(), bias.data_ptr(), M, N, K, 0, 0,
+                        ws.data_ptr(), 1024, stream()), "gemm")
+    acc = torch.full((M, N), 0.5, dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), acc.data_ptr(), None, M, N, K, 1, 1,
+                            ws.data_ptr(), ws.numel() * 4, stream()), "gemm")
     sync()
     assert_close(np64(acc) - 0.5, 2 * want, dtype, "C +=")
 

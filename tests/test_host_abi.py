@@ -138,9 +138,9 @@ def test_chunk_object_errors_without_device_work():
 
 
 def test_single_kernel_argument_checks():
-    assert B.ptdp_gemm(B.BF16, B.GEMM_NN, 256, 256, 256, None, 8, 8, 12, 0, 0, None) == B.E_INVALID_ARG   # K % 8
-    assert B.ptdp_gemm(B.BF16, 5, 256, 256, 256, None, 8, 8, 8, 0, 0, None) == B.E_INVALID_ARG
-    assert B.ptdp_gemm(B.BF16, B.GEMM_NN, None, 256, 256, None, 8, 8, 8, 0, 0, None) == B.E_NULL_PTR
+    assert B.ptdp_gemm(B.BF16, B.GEMM_NN, 256, 256, 256, None, 8, 8, 12, 0, 0, None, 0, None) == B.E_INVALID_ARG   # K % 8
+    assert B.ptdp_gemm(B.BF16, 5, 256, 256, 256, None, 8, 8, 8, 0, 0, None, 0, None) == B.E_INVALID_ARG
+    assert B.ptdp_gemm(B.BF16, B.GEMM_NN, None, 256, 256, None, 8, 8, 8, 0, 0, None, 0, None) == B.E_NULL_PTR
     assert B.ptdp_layernorm_fwd(B.F32, 256, 256, 256, 256, 256, 256, None, 4, 12, 1e-5, None) == B.E_INVALID_ARG
     assert B.ptdp_layernorm_fwd(B.F32, 256, 256, 256, 256, 256, 256, None, 4, 32768, 1e-5, None) == B.E_UNSUPPORTED
     assert B.ptdp_bias_dropout_add_fwd(B.F32, 256, 256, 256, 256, 4, 16, 1.5, 0, 0, 0, 0, None) == B.E_INVALID_ARG
