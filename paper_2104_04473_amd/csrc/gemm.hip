@@ -244,36 +244,78 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kB
 }
 
 // Output forms.  32x32 accumulator layout: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane/32) + r%4.
-enum { OUT_BF16 = 0, OUT_F32_STORE = 1, OUT_F32_ADD = 2 };
+//   OUT_BF16 / OUT_F32_STORE / OUT_F32_RMW: each wave passes its 32-row slabs through its own LDS patch
+//     (the operand stages are free by then) and leaves with 16 consecutive lanes covering one 256-byte
+//     row segment: 16-byte fp32 or 8-byte bf16 accesses instead of scalar ones.
+//   OUT_F32_ADD: fp32 atomic adds straight from the accumulator layout (several workgroups per tile).
+enum { OUT_BF16 = 0, OUT_F32_STORE = 1, OUT_F32_RMW = 2, OUT_F32_ADD = 3 };
+constexpr int kEpiStride = 72;  // floats per staged row of 64: rows 4 apart land 32 banks apart
+
 template <int OUT, int WGM, int WGN>
 __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[kBM / WGM / 32][kBN / WGN / 32], void* Cv, size_t ldc,
-                                              const bf16_t* bias, int M, int N, int m0, int n0) {
+                                              const bf16_t* bias, int M, int N, int m0, int n0, char* smem) {
   constexpr int WM = kBM / WGM, WN = kBN / WGN, TM = WM / 32, TN = WN / 32;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+  if (OUT == OUT_F32_ADD) {
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = n0 + wn0 + j * 32 + (lane & 31);
-    if (n >= N) continue;
-    const float bv = bias ? bf16_to_f32(bias[n]) : 0.f;
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn0 + j * 32 + (lane & 31);
+      if (n >= N) continue;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+      for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m >= M) continue;
-        const float val = acc[i][j][r] + bv;
-        if (OUT == OUT_BF16) {
-          reinterpret_cast<bf16_t*>(Cv)[(size_t)m * ldc + n] = f32_to_bf16(val);
-        } else if (OUT == OUT_F32_STORE) {
-          reinterpret_cast<float*>(Cv)[(size_t)m * ldc + n] = val;
-        } else {
-          // the add happens in L2; within one launch every element is touched by a fixed set of
-          // workgroups, so only the order of a few fp32 additions can vary
-          unsafeAtomicAdd(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n, val);
+        for (int r = 0; r < 16; ++r) {
+          const int m = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          // the add happens in L2; a tile is touched by a fixed set of workgroups, so only the order of
+          // a few fp32 additions can vary between runs
+          if (m < M) unsafeAtomicAdd(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n, acc[i][j][r]);
         }
       }
     }
+    return;
+  }
+  static_assert(WN == 64, "staging patch is 32 rows x 64 columns per wave");
+  float* patch = reinterpret_cast<float*>(smem) + wave * (32 * kEpiStride);
+  float bv[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = n0 + wn0 + j * 32 + (lane & 31);
+    bv[j] = (bias && n < N) ? bf16_to_f32(bias[n]) : 0.f;
+  }
+  const int c4 = (lane & 15) * 4;            // first of this lane's 4 columns inside the wave's 64
+  const int n = n0 + wn0 + c4;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        patch[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kEpiStride + j * 32 + (lane & 31)] = acc[i][j][r] + bv[j];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int row = it * 4 + (lane >> 4);
+      const int m = m0 + wm0 + i * 32 + row;
+      const float4 v = *reinterpret_cast<const float4*>(patch + row * kEpiStride + c4);
+      if (m < M && n < N) {
+        if (OUT == OUT_BF16) {
+          uint2 o;
+          o.x = pack_bf16x2(v.x, v.y);
+          o.y = pack_bf16x2(v.z, v.w);
+          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + (size_t)m * ldc + n) = o;
+        } else {
+          float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n);
+          if (OUT == OUT_F32_RMW) {
+            const float4 o = *c;
+            *c = make_float4(o.x + v.x, o.y + v.y, o.z + v.z, o.w + v.w);
+          } else {
+            *c = v;
+          }
+        }
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
@@ -305,7 +347,7 @@ gemm_bf16_dp_kernel(GemmArgs g, void* Cv) {
   f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
   zero_acc(acc);
   gemm_mainloop<TA, TB, WGM, WGN>(acc, g, tile_m * kBM, tile_n * kBN, 0, (g.K + BK - 1) / BK, smem);
-  gemm_epilogue<OUT, WGM, WGN>(acc, Cv, g.ldc, g.bias, g.M, g.N, tile_m * kBM, tile_n * kBN);
+  gemm_epilogue<OUT, WGM, WGN>(acc, Cv, g.ldc, g.bias, g.M, g.N, tile_m * kBM, tile_n * kBN, smem);
 }
 
 // "Stream-K" form for a tile count that does not fill the machine evenly: the (tile, k-tile) iteration
@@ -328,7 +370,7 @@ gemm_bf16_sk_kernel(GemmArgs g, float* Cacc, size_t ldacc) {
     f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
     zero_acc(acc);
     gemm_mainloop<TA, TB, WGM, WGN>(acc, g, m0, n0, kt0, kt1, smem);
-    gemm_epilogue<OUT_F32_ADD, WGM, WGN>(acc, Cacc, ldacc, nullptr, g.M, g.N, m0, n0);
+    gemm_epilogue<OUT_F32_ADD, WGM, WGN>(acc, Cacc, ldacc, nullptr, g.M, g.N, m0, n0, smem);
     it += kt1 - kt0;
   }
 }
@@ -435,7 +477,7 @@ static int launch_bf16_mode(const void* A, const void* B, void* C, const void* b
     d.N = n_dp;
     int rc;
     if (!out_f32) rc = launch_dp<TA, TB, OUT_BF16>(d, C, st);
-    else if (accumulate) rc = launch_dp<TA, TB, OUT_F32_ADD>(d, C, st);
+    else if (accumulate) rc = launch_dp<TA, TB, OUT_F32_RMW>(d, C, st);
     else rc = launch_dp<TA, TB, OUT_F32_STORE>(d, C, st);
     if (rc != PTDP_OK) return rc;
   }
