@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="first run a plain 1 GiB read + 1 GiB write kernel (scale reference for FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-sample-positions", type=int, default=0, help="sequence positions of the oracle sample")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -68,6 +70,13 @@ def main():
     shape = (w["s"], w["b"], w["h"])
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
+
+    if args.pmc_calibrate:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        for _ in range(3):
+            dst = src * 1.0                                              # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- resident state -------------------------------------------------------------------------
     chunks, params, grads = [], [], []
@@ -151,9 +160,10 @@ def main():
     dms, dwork, dl = gemm[dom]
     all_ms = sum(v[0] for v in gemm.values())
     all_work = sum(v[1] for v in gemm.values())
+    traffic = measured_traffic(args.workload, dom)
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dwork / (dms * 1e-3) / 1e12, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(dwork / (dms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                "traffic": None, "flops_per_launch": dwork / dl, "avg_launch_ms": round(dms / dl, 5),
+                "traffic": traffic, "flops_per_launch": dwork / dl, "avg_launch_ms": round(dms / dl, 5),
                 "all_gemm_achieved": round(all_work / (all_ms * 1e-3) / 1e12, 2),
                 "all_gemm_share_of_step": round(all_ms / prof_steps / ms_per_step, 4)}
 
@@ -175,6 +185,20 @@ def main():
         "context": "paper: 163 TFLOP/s per A100 = 52% of peak, end-to-end on 3072 GPUs, recompute counted (x4)",
     }
     print(json.dumps(out))
+
+
+def measured_traffic(workload, family):
+    """HBM bytes per library call of `family` from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
+    workload (profiles/<workload>_hbm_traffic.txt), or None when no summary exists."""
+    path = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % workload)
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 6 and f[0] == "family" and f[1] == family:
+                return int((float(f[3]) + float(f[5])) * 2 ** 20)
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(w, params_dev, positions):
