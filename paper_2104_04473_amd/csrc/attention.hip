@@ -7,7 +7,7 @@
 //
 // bf16 forward: S^T = K Q^T and O^T = V^T P^T on v_mfma_f32_32x32x16_bf16, so that the softmax
 // probabilities leave the first MFMA already in the register layout the second one wants as its
-// B operand.  One wave owns 32 queries; a block of 4 waves shares 64-key K and V^T tiles in LDS.
+// B operand.  One wave owns 32 queries; a block of 2 waves shares 64-key K and V tiles in LDS.
 // The "rowwise" kernels are the plain formulation (one wave per row): they are the fp32 path and the
 // reference-shaped fallback of the bf16 backward.
 #include "common.h"
@@ -181,71 +181,71 @@ attn_bwd_dkv_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, cons
 }
 
 // ------------------------------------------------------------------------------------------------
-// bf16 MFMA forward
+// bf16 MFMA kernels.  A workgroup is 2 waves and owns 64 queries (forward, dQ) or 64 keys (dK/dV); the
+// other side streams through LDS in tiles of 64 rows kept in memory order [row][dh].  Operands whose
+// contraction index is the tile row (V^T, K^T, Q^T, dO^T) are gathered from those same tiles with
+// transposing LDS reads, so nothing is transposed in registers and every tile is stored once.
 // ------------------------------------------------------------------------------------------------
-constexpr int kBQ = 128;   // queries per block (4 waves x 32)
-constexpr int kBKV = 64;   // keys per LDS tile
-constexpr int kVtStride = kBKV * 2 + 16;   // bytes per V^T row (64 keys) + pad
+constexpr int kBQ = 64;            // rows owned by a workgroup (2 waves x 32)
+constexpr int kBKV = 64;           // rows per streamed LDS tile
+constexpr int kAttnThreads = 128;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
 
-// 8x8 transpose of 16-bit values: in[j] = 8 values of source row j; out[r] = element r of rows 0..7.
-__device__ __forceinline__ void transpose8x8_b16(const uint4 (&in)[8], uint4 (&out)[8]) {
-  const uint32_t* w = reinterpret_cast<const uint32_t*>(&in[0]);
-#pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    uint32_t o[4];
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      const uint32_t x = w[(2 * d) * 4 + (r >> 1)], y = w[(2 * d + 1) * 4 + (r >> 1)];
-      o[d] = (r & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
-    }
-    out[r] = make_uint4(o[0], o[1], o[2], o[3]);
-  }
-}
+// bytes per LDS tile row: padded so that both the 16-byte fragment reads of 16 neighbouring rows and
+// the 4-row x 32-byte gathers of the transposing reads spread over the banks
+template <int DH> struct TileGeom {
+  static constexpr int STRIDE = DH * 2 + (DH == 128 ? 32 : 16);
+  static constexpr int BYTES = kBKV * STRIDE;
+  static constexpr int NCH = kBKV * (DH / 8) / kAttnThreads;  // 16-byte chunks per thread and tile
+};
 
-// Cooperative (256 threads) staging of a 64-row tile of one head: rows row0 .. row0+63 of `src`
-// (row stride rs elements, DH columns), rows >= s zero-filled.
-//   direct:     lds[row][dh], KSTRIDE bytes per row
-//   transposed: lds[dh][row], kVtStride bytes per row (8x8 register transposes)
-template <int DH>
-__device__ __forceinline__ void stage_direct(char* lds, const bf16_t* __restrict__ src, size_t rs, int row0, int s) {
-  constexpr int KSTRIDE = DH * 2 + 16;
-  for (int v = threadIdx.x; v < kBKV * (DH / 8); v += 256) {
-    const int row = v / (DH / 8), ch = v % (DH / 8);
-    uint4 t = make_uint4(0, 0, 0, 0);
-    if (row0 + row < s) t = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + row) * rs + ch * 8);
-    *reinterpret_cast<uint4*>(lds + row * KSTRIDE + ch * 16) = t;
-  }
-}
-template <int DH>
-__device__ __forceinline__ void stage_transposed(char* lds, const bf16_t* __restrict__ src, size_t rs, int row0, int s) {
-  for (int blk = threadIdx.x; blk < 8 * (DH / 8); blk += 256) {
-    const int rg = blk & 7, dg = blk >> 3;
-    uint4 in[8], out[8];
+// One 64-row tile of one head on its way global -> registers -> LDS (rows >= s read as zeros).
+template <int DH> struct TileRegs {
+  uint4 v[TileGeom<DH>::NCH];
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ src, size_t rs, int row0, int s) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      const int row = row0 + rg * 8 + r;
-      in[r] = row < s ? *reinterpret_cast<const uint4*>(src + (size_t)row * rs + dg * 8) : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < TileGeom<DH>::NCH; ++i) {
+      const int c = threadIdx.x + i * kAttnThreads;
+      const int row = c / (DH / 8), ch = c % (DH / 8);
+      // branch-free: read a clamped (always valid) row, then blank it if it is past the end, so that
+      // the loads of a tile are issued back to back
+      const int rr = min(row0 + row, s - 1);
+      const uint4 t = *reinterpret_cast<const uint4*>(src + (size_t)rr * rs + ch * 8);
+      const bool ok = row0 + row < s;
+      v[i] = make_uint4(ok ? t.x : 0u, ok ? t.y : 0u, ok ? t.z : 0u, ok ? t.w : 0u);
     }
-    transpose8x8_b16(in, out);
-#pragma unroll
-    for (int r = 0; r < 8; ++r) *reinterpret_cast<uint4*>(lds + (dg * 8 + r) * kVtStride + rg * 16) = out[r];
   }
-}
-// MFMA A-operand fragment of a direct tile: row = lane & 31 (+32*sub), eight consecutive dh of k16 step kk.
+  __device__ __forceinline__ void store(char* lds) const {
+#pragma unroll
+    for (int i = 0; i < TileGeom<DH>::NCH; ++i) {
+      const int c = threadIdx.x + i * kAttnThreads;
+      const int row = c / (DH / 8), ch = c % (DH / 8);
+      *reinterpret_cast<uint4*>(lds + row * TileGeom<DH>::STRIDE + ch * 16) = v[i];
+    }
+  }
+};
+
+// MFMA fragment with the tile row as the MFMA row: row = sub*32 + (lane & 31), eight consecutive dh of k16 step kk.
 template <int DH>
 __device__ __forceinline__ bf16x8_t frag_direct(const char* lds, int sub, int kk, int l31, int half) {
-  constexpr int KSTRIDE = DH * 2 + 16;
-  return *reinterpret_cast<const bf16x8_t*>(lds + (sub * 32 + l31) * KSTRIDE + (kk * 2 + half) * 16);
+  return *reinterpret_cast<const bf16x8_t*>(lds + (sub * 32 + l31) * TileGeom<DH>::STRIDE + (kk * 2 + half) * 16);
 }
-// MFMA A-operand fragment of a transposed tile: row = dh index d*32 + (lane & 31); its eight tile rows
-// (keys or queries) are taken in the order of the 32x32 accumulator rows that feed the B operand:
-// 16*ks + 4*half + 0..3 and 16*ks + 8 + 4*half + 0..3 inside 32-row half `sub`.
-__device__ __forceinline__ bf16x8_t frag_transposed(const char* lds, int d, int sub, int ks, int l31, int half) {
-  const char* row = lds + (d * 32 + l31) * kVtStride + (sub * 32 + ks * 16 + 4 * half) * 2;
-  const uint2 lo = *reinterpret_cast<const uint2*>(row);
-  const uint2 hi = *reinterpret_cast<const uint2*>(row + 16);
-  uint4 t = make_uint4(lo.x, lo.y, hi.x, hi.y);
-  return *reinterpret_cast<bf16x8_t*>(&t);
+// MFMA fragment with dh as the MFMA row (d*32 + (lane & 31)) and tile rows as the contraction index, taken in
+// the order of the 32x32 accumulator rows that feed the other operand: rows 16*ks + 4*half + 0..3 and
+// 16*ks + 8 + 4*half + 0..3 of 32-row half `sub`.  ds_read_b64_tr_b16: within 16 lanes, lane i receives
+// element (i & 3) of the 8-byte rows addressed by lanes (i >> 2) + {0, 4, 8, 12}.
+template <int DH>
+__device__ __forceinline__ bf16x8_t frag_tr(const char* lds, int d, int sub, int ks, int lane) {
+  const int r = lane & 15, G = lane >> 4;
+  const int dh0 = d * 32 + 16 * (G & 1) + 4 * (r & 3);
+  const int row = sub * 32 + ks * 16 + 4 * (G >> 1) + (r >> 2);
+  const char* p = lds + row * TileGeom<DH>::STRIDE + dh0 * 2;
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
+  const s16x4_t hi =
+      __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p + 8 * TileGeom<DH>::STRIDE));
+  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
+  s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return *reinterpret_cast<bf16x8_t*>(&v);
 }
 // Registers 8*ks .. 8*ks+7 of a 32x32 accumulator as a bf16 B-operand fragment.
 __device__ __forceinline__ bf16x8_t pack_frag(const f32x16_t& a, int ks) {
@@ -260,9 +260,10 @@ __device__ __forceinline__ f32x16_t zero16() {
   return z;
 }
 // lane's 8 consecutive dh (k16 step kk) of one token row, as a B-operand fragment straight from HBM
-__device__ __forceinline__ bf16x8_t frag_global(const bf16_t* row_or_null, int kk, int half) {
-  uint4 t = make_uint4(0, 0, 0, 0);
-  if (row_or_null) t = *reinterpret_cast<const uint4*>(row_or_null + kk * 16 + half * 8);
+// (`row` must be readable; `ok` false blanks the fragment)
+__device__ __forceinline__ bf16x8_t frag_global(const bf16_t* row, bool ok, int kk, int half) {
+  const uint4 r = *reinterpret_cast<const uint4*>(row + kk * 16 + half * 8);
+  uint4 t = make_uint4(ok ? r.x : 0u, ok ? r.y : 0u, ok ? r.z : 0u, ok ? r.w : 0u);
   return *reinterpret_cast<bf16x8_t*>(&t);
 }
 // accumulator rows (dh) of lane's column (token) -> 8-byte stores of 4 consecutive dh
@@ -279,18 +280,37 @@ __device__ __forceinline__ void store_cols(bf16_t* out_row, const f32x16_t (&acc
     }
 }
 
+// Work assignment.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: every block of one
+// (sample, head) pair goes to the same XCD so that the pair's K and V stay in that L2, and each XCD
+// takes its pairs one after the other.  Returns false for surplus ids.  `blk` counts up within a pair.
+__device__ __forceinline__ bool attn_map(int id, int nblk, int heads, int b, int* blk, int* e, int* j) {
+  const int xcd = id & 7, local = id >> 3;
+  const int pair = xcd + 8 * (local / nblk);
+  if (pair >= heads * b) return false;
+  *blk = local % nblk;
+  *e = pair % heads;
+  *j = pair / heads;
+  return true;
+}
+inline int attn_grid(int nblk, int heads, int b) { return 8 * ((heads * b + 7) / 8) * nblk; }
+
+// Forward: S^T = K Q^T and O^T = V^T P^T, so that the probabilities leave the first MFMA in the register
+// layout the second one takes as its B operand.  Tiles pass through few registers on purpose: two or
+// three workgroups share a CU and hide each other's load latency, which needs the register budget
+// more than a software prefetch does.
 template <int DH>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kAttnThreads, 2)
 attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* __restrict__ lse, int s, int b,
               int heads) {
-  constexpr int KSTRIDE = DH * 2 + 16;  // bytes per K row in LDS
-  constexpr int NKK = DH / 16;          // k16 steps over dh
-  constexpr int NDT = DH / 32;          // 32-row tiles of O^T
-  __shared__ __attribute__((aligned(16))) char k_lds[kBKV * KSTRIDE];
-  __shared__ __attribute__((aligned(16))) char vt_lds[DH * kVtStride];
+  constexpr int NKK = DH / 16, NDT = DH / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* k_lds = smem;
+  char* v_lds = smem + TileGeom<DH>::BYTES;
 
-  const int qblk = gridDim.x - 1 - blockIdx.x;  // long rows first
-  const int e = blockIdx.y, j = blockIdx.z;
+  const int nqb = (s + kBQ - 1) / kBQ;
+  int qblk, e, j;
+  if (!attn_map(blockIdx.x, nqb, heads, b, &qblk, &e, &j)) return;
+  qblk = nqb - 1 - qblk;  // long rows first
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
   const int hp = heads * DH;
   const size_t rs = (size_t)b * 3 * hp;
@@ -299,10 +319,9 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
   const int my_q = q_first + l31;
   const float c2 = rsqrtf((float)DH) * 1.4426950408889634f;  // scale * log2(e)
 
-  // Q^T fragments (B operand): lane = query, 8 consecutive dh per k16 step
   bf16x8_t qf[NKK];
 #pragma unroll
-  for (int kk = 0; kk < NKK; ++kk) qf[kk] = frag_global(my_q < s ? base + (size_t)my_q * rs : nullptr, kk, half);
+  for (int kk = 0; kk < NKK; ++kk) qf[kk] = frag_global(base + (size_t)min(my_q, s - 1) * rs, my_q < s, kk, half);
 
   f32x16_t o[NDT];
 #pragma unroll
@@ -311,15 +330,17 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
 
   const int q_last_blk = min(s, (qblk + 1) * kBQ) - 1;
   const int ntiles = q_last_blk / kBKV + 1;
+  TileRegs<DH> kr;
   for (int kt = 0; kt < ntiles; ++kt) {
     const int key0 = kt * kBKV;
     __syncthreads();
-    stage_direct<DH>(k_lds, base + hp, rs, key0, s);
-    stage_transposed<DH>(vt_lds, base + 2 * hp, rs, key0, s);
+    kr.load(base + hp, rs, key0, s);
+    kr.store(k_lds);
+    kr.load(base + 2 * hp, rs, key0, s);
+    kr.store(v_lds);
     __syncthreads();
     if (key0 > q_first + 31) continue;  // every key of the tile is in this wave's future
 
-    // S^T[key][query] for the two 32-key halves of the tile
     f32x16_t sacc[2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -348,7 +369,6 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
     for (int d = 0; d < NDT; ++d)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[d][r] *= corr;
-    // P^T as B operand: registers 8*ks .. 8*ks+7 of each half tile serve k16 step ks
     bf16x8_t pf[2][2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -360,15 +380,13 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
       pf[sub][0] = pack_frag(sacc[sub], 0);
       pf[sub][1] = pack_frag(sacc[sub], 1);
     }
-    // O^T[dh][query] += V^T[dh][key] P^T[key][query]
 #pragma unroll
     for (int d = 0; d < NDT; ++d)
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(vt_lds, d, sub, ks, l31, half), pf[sub][ks],
-                                                         o[d], 0, 0, 0);
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(v_lds, d, sub, ks, lane), pf[sub][ks], o[d], 0, 0, 0);
   }
   l_run += __shfl_xor(l_run, 32, 64);
   if (my_q < s) {
@@ -379,21 +397,22 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
 
 // ------------------------------------------------------------------------------------------------
 // bf16 MFMA backward.  P is recomputed from the stashed log-sum-exp; two kernels so that no result
-// needs atomics: one owns 128 queries and produces dQ, one owns 128 keys and produces dK and dV.
+// needs atomics: one owns 64 queries and produces dQ, one owns 64 keys and produces dK and dV.
 //   dP = dO V^T, dS = P o (dP - delta), dQ = dS K / sqrt(dh), dK = dS^T Q / sqrt(dh), dV = P^T dO
 // ------------------------------------------------------------------------------------------------
 template <int DH>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kAttnThreads, 2)
 attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
                  const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads) {
-  constexpr int KSTRIDE = DH * 2 + 16, NKK = DH / 16, NDT = DH / 32;
+  constexpr int NKK = DH / 16, NDT = DH / 32;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  char* k_lds = smem;                         // K   [key][dh]
-  char* v_lds = k_lds + kBKV * KSTRIDE;       // V   [key][dh]
-  char* kt_lds = v_lds + kBKV * KSTRIDE;      // K^T [dh][key]
+  char* k_lds = smem;                          // K [key][dh]: S^T = K Q^T directly, dQ^T = K^T dS^T through tr reads
+  char* v_lds = smem + TileGeom<DH>::BYTES;    // V [key][dh]: dP^T = V dO^T
 
-  const int qblk = gridDim.x - 1 - blockIdx.x;
-  const int e = blockIdx.y, j = blockIdx.z;
+  const int nqb = (s + kBQ - 1) / kBQ;
+  int qblk, e, j;
+  if (!attn_map(blockIdx.x, nqb, heads, b, &qblk, &e, &j)) return;
+  qblk = nqb - 1 - qblk;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
   const int hp = heads * DH;
   const size_t rs = (size_t)b * 3 * hp;
@@ -407,11 +426,11 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
   const float D = valid ? delta[stat] : 0.f;
 
   bf16x8_t qf[NKK], dof[NKK];
-  const bf16_t* dorow = dctx + ((size_t)my_q * b + j) * hp + (size_t)e * DH;
+  const bf16_t* dorow = dctx + ((size_t)min(my_q, s - 1) * b + j) * hp + (size_t)e * DH;
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
-    qf[kk] = frag_global(valid ? base + (size_t)my_q * rs : nullptr, kk, half);
-    dof[kk] = frag_global(valid ? dorow : nullptr, kk, half);
+    qf[kk] = frag_global(base + (size_t)min(my_q, s - 1) * rs, valid, kk, half);
+    dof[kk] = frag_global(dorow, valid, kk, half);
   }
   f32x16_t acc[NDT];
 #pragma unroll
@@ -419,12 +438,14 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
 
   const int q_last_blk = min(s, (qblk + 1) * kBQ) - 1;
   const int ntiles = q_last_blk / kBKV + 1;
+  TileRegs<DH> kr;
   for (int kt = 0; kt < ntiles; ++kt) {
     const int key0 = kt * kBKV;
     __syncthreads();
-    stage_direct<DH>(k_lds, base + hp, rs, key0, s);
-    stage_direct<DH>(v_lds, base + 2 * hp, rs, key0, s);
-    stage_transposed<DH>(kt_lds, base + hp, rs, key0, s);
+    kr.load(base + hp, rs, key0, s);
+    kr.store(k_lds);
+    kr.load(base + 2 * hp, rs, key0, s);
+    kr.store(v_lds);
     __syncthreads();
     if (key0 > q_first + 31) continue;
     bf16x8_t dsf[2][2];
@@ -451,27 +472,24 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
-          acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(kt_lds, d, sub, ks, l31, half), dsf[sub][ks],
-                                                           acc[d], 0, 0, 0);
+          acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(k_lds, d, sub, ks, lane), dsf[sub][ks], acc[d], 0, 0, 0);
   }
   if (valid) store_cols<NDT>(dqkv + (size_t)my_q * rs + (size_t)j * 3 * hp + (size_t)e * DH, acc, scale, half);
 }
 
 template <int DH>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(kAttnThreads)
 attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
                   const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads) {
-  constexpr int KSTRIDE = DH * 2 + 16, NKK = DH / 16, NDT = DH / 32;
+  constexpr int NKK = DH / 16, NDT = DH / 32;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  char* q_lds = smem;                          // Q    [query][dh]
-  char* do_lds = q_lds + kBKV * KSTRIDE;       // dO   [query][dh]
-  char* qt_lds = do_lds + kBKV * KSTRIDE;      // Q^T  [dh][query]
-  char* dot_lds = qt_lds + DH * kVtStride;     // dO^T [dh][query]
-  float* lse_lds = reinterpret_cast<float*>(dot_lds + DH * kVtStride);  // lse * log2(e), +inf past the end
+  char* q_lds = smem;                           // Q  [query][dh]: S = Q K^T directly, dK^T = Q^T dS through tr reads
+  char* do_lds = smem + TileGeom<DH>::BYTES;    // dO [query][dh]: dP = dO V^T directly, dV^T = dO^T P through tr reads
+  float* lse_lds = reinterpret_cast<float*>(smem + 2 * TileGeom<DH>::BYTES);  // lse * log2(e), +inf past the end
   float* delta_lds = lse_lds + kBKV;
 
-  const int kblk = blockIdx.x;  // the first key blocks see the most queries and start first
-  const int e = blockIdx.y, j = blockIdx.z;
+  int kblk, e, j;  // the first key blocks see the most queries and start first
+  if (!attn_map(blockIdx.x, (s + kBQ - 1) / kBQ, heads, b, &kblk, &e, &j)) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
   const int hp = heads * DH;
   const size_t rs = (size_t)b * 3 * hp;
@@ -488,8 +506,8 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
   bf16x8_t kf[NKK], vf[NKK];
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
-    kf[kk] = frag_global(valid ? base + (size_t)my_key * rs + hp : nullptr, kk, half);
-    vf[kk] = frag_global(valid ? base + (size_t)my_key * rs + 2 * hp : nullptr, kk, half);
+    kf[kk] = frag_global(base + (size_t)min(my_key, s - 1) * rs + hp, valid, kk, half);
+    vf[kk] = frag_global(base + (size_t)min(my_key, s - 1) * rs + 2 * hp, valid, kk, half);
   }
   f32x16_t dk[NDT], dv[NDT];
 #pragma unroll
@@ -501,10 +519,13 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
   for (int qt = (kblk * kBQ) / kBKV; qt < nq_tiles; ++qt) {
     const int q0 = qt * kBKV;
     __syncthreads();
-    stage_direct<DH>(q_lds, base, rs, q0, s);
-    stage_direct<DH>(do_lds, dobase, dors, q0, s);
-    stage_transposed<DH>(qt_lds, base, rs, q0, s);
-    stage_transposed<DH>(dot_lds, dobase, dors, q0, s);
+    {
+      TileRegs<DH> t;
+      t.load(base, rs, q0, s);
+      t.store(q_lds);
+      t.load(dobase, dors, q0, s);
+      t.store(do_lds);
+    }
     if (threadIdx.x < kBKV) {
       const int q = q0 + threadIdx.x;
       lse_lds[threadIdx.x] = q < s ? lse_h[q] * 1.4426950408889634f : INFINITY;
@@ -546,10 +567,8 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-          dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(dot_lds, d, sub, ks, l31, half), pf[sub][ks],
-                                                          dv[d], 0, 0, 0);
-          dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_transposed(qt_lds, d, sub, ks, l31, half), dsf[sub][ks],
-                                                          dk[d], 0, 0, 0);
+          dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(do_lds, d, sub, ks, lane), pf[sub][ks], dv[d], 0, 0, 0);
+          dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(q_lds, d, sub, ks, lane), dsf[sub][ks], dk[d], 0, 0, 0);
         }
   }
   if (valid) {
@@ -598,22 +617,38 @@ bool attn_dh_supported(int dtype, int dh) {
 
 static inline double attn_flops(int s, int b, int heads, int dh) { return 4.0 * b * heads * (double)s * s * dh; }
 
+template <int DH>
+static int attn_fwd_mfma_t(const bf16_t* qkv, bf16_t* ctx, float* lse, int s, int b, int heads, hipStream_t stream) {
+  constexpr int smem = 2 * TileGeom<DH>::BYTES;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_mfma<DH>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            smem) != hipSuccess)
+      return PTDP_E_HIP;
+    attr_set = true;
+  }
+  const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
+  hipLaunchKernelGGL((attn_fwd_mfma<DH>), grid, dim3(kAttnThreads), smem, stream, qkv, ctx, lse, s, b, heads);
+  return PTDP_OK;
+}
+
 int launch_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, int b, int heads, int dh,
                     hipStream_t stream) {
   if (s == 0 || b == 0 || heads == 0) return PTDP_OK;
   if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
   Launch L(PTDP_K_ATTN_FWD, attn_flops(s, b, heads, dh), stream);
+  int rc = PTDP_OK;
   if (dtype == PTDP_F32) {
     hipLaunchKernelGGL((attn_fwd_rowwise<float>), dim3(s, heads, b), dim3(64), 0, stream, (const float*)qkv,
                        (float*)ctx, lse, s, b, heads, dh);
   } else {
-    const dim3 grid((s + kBQ - 1) / kBQ, heads, b);
     const bf16_t* q = (const bf16_t*)qkv;
     bf16_t* c = (bf16_t*)ctx;
-    if (dh == 64) hipLaunchKernelGGL((attn_fwd_mfma<64>), grid, dim3(256), 0, stream, q, c, lse, s, b, heads);
-    else if (dh == 128) hipLaunchKernelGGL((attn_fwd_mfma<128>), grid, dim3(256), 0, stream, q, c, lse, s, b, heads);
-    else hipLaunchKernelGGL((attn_fwd_mfma<160>), grid, dim3(256), 0, stream, q, c, lse, s, b, heads);
+    if (dh == 64) rc = attn_fwd_mfma_t<64>(q, c, lse, s, b, heads, stream);
+    else if (dh == 128) rc = attn_fwd_mfma_t<128>(q, c, lse, s, b, heads, stream);
+    else rc = attn_fwd_mfma_t<160>(q, c, lse, s, b, heads, stream);
   }
+  if (rc != PTDP_OK) return rc;
   return L.status();
 }
 
@@ -633,9 +668,8 @@ static int attn_bwd_rowwise_t(const void* qkv, const void* ctx, const float* lse
 template <int DH>
 static int attn_bwd_mfma_t(const bf16_t* qkv, const bf16_t* ctx, const float* lse, const bf16_t* dctx, bf16_t* dqkv,
                            float* delta, int s, int b, int heads, hipStream_t stream) {
-  constexpr int KSTRIDE = DH * 2 + 16;
-  constexpr int smem_dq = 2 * kBKV * KSTRIDE + DH * kVtStride;
-  constexpr int smem_dkv = 2 * kBKV * KSTRIDE + 2 * DH * kVtStride + 2 * kBKV * (int)sizeof(float);
+  constexpr int smem_dq = 2 * TileGeom<DH>::BYTES;
+  constexpr int smem_dkv = 2 * TileGeom<DH>::BYTES + 2 * kBKV * (int)sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq_mfma<DH>),
@@ -648,9 +682,9 @@ static int attn_bwd_mfma_t(const bf16_t* qkv, const bf16_t* ctx, const float* ls
   const size_t rows = (size_t)s * b * heads;
   hipLaunchKernelGGL(attn_delta_bf16, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, ctx, dctx, delta, s, b,
                      heads, DH);
-  const dim3 grid((s + kBQ - 1) / kBQ, heads, b);
-  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH>), grid, dim3(256), smem_dkv, stream, qkv, dctx, lse, delta, dqkv, s, b, heads);
-  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH>), grid, dim3(256), smem_dq, stream, qkv, dctx, lse, delta, dqkv, s, b, heads);
+  const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH>), grid, dim3(kAttnThreads), smem_dkv, stream, qkv, dctx, lse, delta, dqkv, s, b, heads);
+  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH>), grid, dim3(kAttnThreads), smem_dq, stream, qkv, dctx, lse, delta, dqkv, s, b, heads);
   return PTDP_OK;
 }
 

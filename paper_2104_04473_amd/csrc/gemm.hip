@@ -307,8 +307,11 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[kBM / WGM / 
         } else {
           float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n);
           if (OUT == OUT_F32_RMW) {
-            const float4 o = *c;
-            *c = make_float4(o.x + v.x, o.y + v.y, o.z + v.z, o.w + v.w);
+            // gradient accumulators are touched once per launch: stream them past the caches
+            typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+            f32x4_t o = __builtin_nontemporal_load(reinterpret_cast<f32x4_t*>(c));
+            o[0] += v.x; o[1] += v.y; o[2] += v.z; o[3] += v.w;
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(c));
           } else {
             *c = v;
           }
