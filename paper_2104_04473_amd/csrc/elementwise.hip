@@ -141,6 +141,7 @@ __global__ void layernorm_bwd_param_kernel(const T* __restrict__ du, const T* __
 #pragma unroll
   for (int j = 0; j < N; ++j) ag[j] = ab[j] = 0.f;
   const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
+#pragma unroll 4
   for (int r = r0; r < r1; ++r) {
     const size_t off = (size_t)r * width + (size_t)c * N;
     const float m = mu[r], rs = rstd[r];
@@ -169,13 +170,22 @@ __global__ void colsum_finish_kernel(const float* __restrict__ part, int nparts,
                                      float* out1, int width) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= width) return;
-  float a = 0.f, b = 0.f;
-  for (int p = 0; p < nparts; ++p) {
-    a += part[(size_t)p * stride + c];
-    if (out1) b += part[(size_t)p * stride + width + c];
+  // four independent partial sums keep several loads in flight; the order of additions is fixed
+  float a[4] = {0.f, 0.f, 0.f, 0.f}, b[4] = {0.f, 0.f, 0.f, 0.f};
+  int p = 0;
+  for (; p + 4 <= nparts; p += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      a[u] += part[(size_t)(p + u) * stride + c];
+      if (out1) b[u] += part[(size_t)(p + u) * stride + width + c];
+    }
   }
-  out0[c] += a;
-  if (out1) out1[c] += b;
+  for (; p < nparts; ++p) {
+    a[0] += part[(size_t)p * stride + c];
+    if (out1) b[0] += part[(size_t)p * stride + width + c];
+  }
+  out0[c] += (a[0] + a[1]) + (a[2] + a[3]);
+  if (out1) out1[c] += (b[0] + b[1]) + (b[2] + b[3]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -230,6 +240,7 @@ __global__ void bias_gelu_bwd_kernel(const T* dg, const T* __restrict__ z, const
 #pragma unroll
   for (int j = 0; j < N; ++j) acc[j] = 0.f;
   const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
+#pragma unroll 4
   for (int r = r0; r < r1; ++r) {
     const size_t off = (size_t)r * width + (size_t)c * N;
     Vec16<T> a, zz;
@@ -297,6 +308,7 @@ __global__ void bda_bwd_kernel(const T* __restrict__ dout, T* __restrict__ din, 
 #pragma unroll
   for (int j = 0; j < N; ++j) acc[j] = 0.f;
   const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
+#pragma unroll 4
   for (int r = r0; r < r1; ++r) {
     const size_t off = (size_t)r * width + (size_t)c * N;
     Vec16<T> a;
@@ -328,6 +340,7 @@ __global__ void colsum_rows_kernel(const T* __restrict__ in, float* __restrict__
 #pragma unroll
   for (int j = 0; j < N; ++j) acc[j] = 0.f;
   const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
+#pragma unroll 4
   for (int r = r0; r < r1; ++r) {
     Vec16<T> a;
     float af[N];
