@@ -264,13 +264,14 @@ int ptdp_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t seed, uint32_t
  * A, B in `dtype`.  out_f32 = 0: C in `dtype`, overwritten; out_f32 = 1: C fp32,
  * accumulated (+=) when accumulate != 0.  bias [N] in `dtype` or NULL.  bf16
  * needs M, N, K multiples of 8 and operands below 2 GiB.  workspace (dev, may
- * be NULL): fp32 scratch of up to M*N*4 bytes; with it, a tile count that does
- * not fill the compute units evenly is finished by splitting the remaining
- * tiles along k (their partial sums are added with fp32 atomics, so the last
- * bits of those outputs may differ between runs). */
+ * be NULL): ptdp_gemm_workspace_bytes() bytes of scratch; with it, a tile count
+ * that does not fill the compute units evenly is finished by cutting the last,
+ * incomplete round of tiles along k: partial tiles go to the workspace and are
+ * summed in a fixed order, so results stay bit-reproducible. */
 enum { PTDP_GEMM_NN = 0, PTDP_GEMM_NT = 1, PTDP_GEMM_TN = 2 };
 int ptdp_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N,
               int K, int out_f32, int accumulate, void* workspace, size_t workspace_bytes, void* stream);
+size_t ptdp_gemm_workspace_bytes(void);
 
 /* Fused causal attention over qkv [s, b, 3hp] (scale 1/sqrt(dh), implicit
  * causal mask, softmax, times V; section 4.2's scale+mask+softmax fusion

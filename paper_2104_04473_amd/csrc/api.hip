@@ -137,10 +137,8 @@ static WsLayout ws_layout(const ptdp_layer_cfg* c) {
   if (c2 > cs) cs = c2;
   if (c3 > cs) cs = c3;
   sz[WS_COLSUM] = cs;
-  // fp32 image of the widest bf16 GEMM output, for output tiles that are split along k
-  int64_t widest = d.fp > d.h ? d.fp : d.h;
-  if (3 * d.hp > widest) widest = 3 * d.hp;
-  sz[WS_SPLITK] = c->dtype == PTDP_BF16 ? (size_t)d.T * widest * sizeof(float) : 0;
+  // partial tiles of GEMMs whose last, incomplete round of tiles is split along k
+  sz[WS_SPLITK] = c->dtype == PTDP_BF16 ? gemm_workspace_bytes() : 0;
   WsLayout L;
   size_t o = 0;
   for (int i = 0; i < WS_N; ++i) {
@@ -554,6 +552,8 @@ int ptdp_bias_dropout_add_bwd(int dtype, const void* dout, void* din, float* dbi
 }
 
 size_t ptdp_colsum_scratch_bytes(int rows, int width) { return colsum_scratch_bytes(rows, width); }
+
+size_t ptdp_gemm_workspace_bytes(void) { return gemm_workspace_bytes(); }
 
 int ptdp_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t seed, uint32_t layer, uint32_t site,
                       uint64_t microbatch, void* stream) {

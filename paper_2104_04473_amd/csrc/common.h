@@ -121,7 +121,8 @@ int launch_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t key, hipStre
 size_t colsum_scratch_bytes(int rows, int width);
 // out[width] (fp32) += column sums of in[rows, width]
 int launch_colsum(int dtype, const void* in, float* out, void* scratch, int rows, int width, hipStream_t st);
-// ws / ws_bytes: optional fp32 scratch for tiles that are split along k (may be null / 0)
+// ws / ws_bytes: optional scratch of gemm_workspace_bytes() for tiles that are split along k (may be null / 0)
+size_t gemm_workspace_bytes();
 int launch_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N,
                 int K, int out_f32, int accumulate, void* ws, size_t ws_bytes, hipStream_t st);
 int launch_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, int b, int heads, int dh,

@@ -244,11 +244,10 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kB
 }
 
 // Output forms.  32x32 accumulator layout: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane/32) + r%4.
-//   OUT_BF16 / OUT_F32_STORE / OUT_F32_RMW: each wave passes its 32-row slabs through its own LDS patch
+//   Each wave passes its 32-row slabs through its own LDS patch
 //     (the operand stages are free by then) and leaves with 16 consecutive lanes covering one 256-byte
 //     row segment: 16-byte fp32 or 8-byte bf16 accesses instead of scalar ones.
-//   OUT_F32_ADD: fp32 atomic adds straight from the accumulator layout (several workgroups per tile).
-enum { OUT_BF16 = 0, OUT_F32_STORE = 1, OUT_F32_RMW = 2, OUT_F32_ADD = 3 };
+enum { OUT_BF16 = 0, OUT_F32_STORE = 1, OUT_F32_RMW = 2 };
 constexpr int kEpiStride = 72;  // floats per staged row of 64: rows 4 apart land 32 banks apart
 
 template <int OUT, int WGM, int WGN>
@@ -257,24 +256,6 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[kBM / WGM / 
   constexpr int WM = kBM / WGM, WN = kBN / WGN, TM = WM / 32, TN = WN / 32;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
-  if (OUT == OUT_F32_ADD) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn0 + j * 32 + (lane & 31);
-      if (n >= N) continue;
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          // the add happens in L2; a tile is touched by a fixed set of workgroups, so only the order of
-          // a few fp32 additions can vary between runs
-          if (m < M) unsafeAtomicAdd(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n, acc[i][j][r]);
-        }
-      }
-    }
-    return;
-  }
   static_assert(WN == 64, "staging patch is 32 rows x 64 columns per wave");
   float* patch = reinterpret_cast<float*>(smem) + wave * (32 * kEpiStride);
   float bv[TN];
@@ -361,54 +342,89 @@ gemm_bf16_dp_kernel(GemmArgs g, void* Cv) {
 }
 
 // "Stream-K" form for a tile count that does not fill the machine evenly: the (tile, k-tile) iteration
-// space is cut into gridDim.x equal contiguous ranges, one per workgroup; every range adds its partial
-// tile(s) into an fp32 matrix (zero, or a gradient accumulator) with L2 atomics.  No workgroup waits
-// for another one.
+// space is cut into gridDim.x equal contiguous ranges, one per workgroup.  A range shorter than one
+// tile's k extent touches at most two tiles; the workgroup stores its partial tile(s) as dense
+// 256 x 256 fp32 slabs (slab 0: the tile its range starts in, slab 1: the next one).  No workgroup
+// waits for another one and nothing is added atomically: gemm_sk_reduce_kernel sums the slabs of each
+// tile in workgroup order, so the result does not depend on timing.
+constexpr size_t kSlabFloats = (size_t)kBM * kBN;
+
+__host__ __device__ inline long long sk_begin(long long total, int blk, int nblk) { return total * blk / nblk; }
+
 template <bool TA, bool TB, int WGM, int WGN>
 __global__ void __launch_bounds__(WGM * WGN * 64)
-gemm_bf16_sk_kernel(GemmArgs g, float* Cacc, size_t ldacc) {
+gemm_bf16_sk_kernel(GemmArgs g, float* slabs) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
   const int nk = (g.K + BK - 1) / BK;
   const long long total = (long long)tiles_m * tiles_n * nk;
-  long long it = total * blockIdx.x / gridDim.x;
-  const long long it_end = total * (blockIdx.x + 1) / gridDim.x;
-  while (it < it_end) {
+  long long it = sk_begin(total, blockIdx.x, gridDim.x);
+  const long long it_end = sk_begin(total, blockIdx.x + 1, gridDim.x);
+  for (int seg = 0; it < it_end && seg < 2; ++seg) {
     const int tile = (int)(it / nk), kt0 = (int)(it % nk);
     const int kt1 = (int)min((long long)nk, kt0 + (it_end - it));
     const int m0 = (tile % tiles_m) * kBM, n0 = (tile / tiles_m) * kBN;
     f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
     zero_acc(acc);
     gemm_mainloop<TA, TB, WGM, WGN>(acc, g, m0, n0, kt0, kt1, smem);
-    gemm_epilogue<OUT_F32_ADD, WGM, WGN>(acc, Cacc, ldacc, nullptr, g.M, g.N, m0, n0, smem);
+    gemm_epilogue<OUT_F32_STORE, WGM, WGN>(acc, slabs + ((size_t)blockIdx.x * 2 + seg) * kSlabFloats, kBN, nullptr, kBM, kBN,
+                                           0, 0, smem);
     it += kt1 - kt0;
   }
 }
 
-// ws[M, N] fp32 -> C[M, ldc] bf16 (+ bias); 4 elements per thread
-__global__ void gemm_sk_convert_kernel(const float* __restrict__ ws, bf16_t* __restrict__ C, const bf16_t* __restrict__ bias,
-                                       int M, int N, size_t ldc) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t nvec = (size_t)N / 4;
-  if (i >= (size_t)M * nvec) return;
-  const size_t m = i / nvec;
-  const int n = (int)(i % nvec) * 4;
-  const float4 v = *reinterpret_cast<const float4*>(ws + m * N + n);
-  float b[4] = {0.f, 0.f, 0.f, 0.f};
-  if (bias) {
-    const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
-    b[0] = __uint_as_float(bb.x << 16); b[1] = __uint_as_float(bb.x & 0xffff0000u);
-    b[2] = __uint_as_float(bb.y << 16); b[3] = __uint_as_float(bb.y & 0xffff0000u);
+// One workgroup per (tile, 16-row band): sums the slabs that cover the tile, in workgroup order, and
+// writes C = sum (+ bias) as bf16, or C += sum as fp32.  nblk is the grid size of the stream-K launch.
+template <bool OUT_F32>
+__global__ void __launch_bounds__(256)
+gemm_sk_reduce_kernel(const float* __restrict__ slabs, void* Cv, const bf16_t* __restrict__ bias, int M, int N, int K,
+                      size_t ldc, int nblk) {
+  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
+  const int nk = (K + BK - 1) / BK;
+  const long long total = (long long)tiles_m * tiles_n * nk;
+  const int tile = blockIdx.x >> 4, band = blockIdx.x & 15;
+  const int row = band * 16 + (threadIdx.x >> 4), c4 = (threadIdx.x & 15) * 4;   // 16 rows x 64 float4 per pass
+  const long long t0 = (long long)tile * nk, t1 = t0 + nk;
+  int blk = (int)(t0 * nblk / total);
+  if (blk > 0) --blk;
+  while (sk_begin(total, blk + 1, nblk) <= t0) ++blk;   // first workgroup whose range reaches into the tile
+  float4 sum[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) sum[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (; blk < nblk && sk_begin(total, blk, nblk) < t1; ++blk) {
+    const long long b0 = sk_begin(total, blk, nblk);
+    if (sk_begin(total, blk + 1, nblk) == b0) continue;               // empty range
+    const int seg = (b0 / nk == tile) ? 0 : 1;
+    const float* slab = slabs + ((size_t)blk * 2 + seg) * kSlabFloats + (size_t)row * kBN + c4;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 v = *reinterpret_cast<const float4*>(slab + q * 64);
+      sum[q].x += v.x; sum[q].y += v.y; sum[q].z += v.z; sum[q].w += v.w;
+    }
   }
-  uint2 o;
-  o.x = pack_bf16x2(v.x + b[0], v.y + b[1]);
-  o.y = pack_bf16x2(v.z + b[2], v.w + b[3]);
-  *reinterpret_cast<uint2*>(C + m * ldc + n) = o;
-}
-
-__global__ void fill_zero_kernel(float4* p, size_t n4) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x)
-    p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int m = (tile % tiles_m) * kBM + row;
+  if (m >= M) return;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int n = (tile / tiles_m) * kBN + q * 64 + c4;
+    if (n >= N) continue;
+    if (OUT_F32) {
+      float4* c = reinterpret_cast<float4*>(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n);
+      const float4 o = *c;
+      *c = make_float4(o.x + sum[q].x, o.y + sum[q].y, o.z + sum[q].z, o.w + sum[q].w);
+    } else {
+      float b[4] = {0.f, 0.f, 0.f, 0.f};
+      if (bias) {
+        const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
+        b[0] = __uint_as_float(bb.x << 16); b[1] = __uint_as_float(bb.x & 0xffff0000u);
+        b[2] = __uint_as_float(bb.y << 16); b[3] = __uint_as_float(bb.y & 0xffff0000u);
+      }
+      uint2 o;
+      o.x = pack_bf16x2(sum[q].x + b[0], sum[q].y + b[1]);
+      o.y = pack_bf16x2(sum[q].z + b[2], sum[q].w + b[3]);
+      *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + (size_t)m * ldc + n) = o;
+    }
+  }
 }
 
 constexpr int kWGM = 2, kWGN = 4, kGemmThreads = kWGM * kWGN * 64, kGemmSmem = 2 * kStageBytes;
@@ -434,11 +450,11 @@ static int launch_dp(const GemmArgs& g, void* C, hipStream_t st) {
 }
 
 template <bool TA, bool TB>
-static int launch_sk(const GemmArgs& g, float* Cacc, size_t ldacc, int blocks, hipStream_t st) {
+static int launch_sk(const GemmArgs& g, float* slabs, int blocks, hipStream_t st) {
   auto kern = gemm_bf16_sk_kernel<TA, TB, kWGM, kWGN>;
   static bool done = false;
   if (set_smem_once(kern, &done) != PTDP_OK) return PTDP_E_HIP;
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, Cacc, ldacc);
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, slabs);
   return PTDP_OK;
 }
 
@@ -453,8 +469,10 @@ static int compute_units() {
   return n;
 }
 
+size_t gemm_workspace_bytes() { return (size_t)compute_units() * 2 * kSlabFloats * sizeof(float); }
+
 // Splits the columns into a part whose tiles fill whole rounds of the machine (one workgroup per tile)
-// and a remainder that is spread evenly over all compute units in stream-K form.
+// and a remainder of less than one round that is spread evenly over all compute units in stream-K form.
 template <bool TA, bool TB>
 static int launch_bf16_mode(const void* A, const void* B, void* C, const void* bias, int M, int N, int K, int out_f32,
                             int accumulate, void* ws, size_t ws_bytes, hipStream_t st) {
@@ -475,12 +493,10 @@ static int launch_bf16_mode(const void* A, const void* B, void* C, const void* b
   const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN, nk = (K + BK - 1) / BK;
   const long long tiles = (long long)tiles_m * tiles_n;
   const int rem = (int)(tiles % ncu);
-  const bool sk_out_ok = (out_f32 && accumulate && !bias) || (!out_f32 && ws != nullptr);
+  const bool sk_out_ok = (out_f32 && accumulate && !bias) || !out_f32;
   int dp_cols = tiles_n;
-  if (sk_out_ok && nk >= 64 && rem != 0 && rem * 100 < ncu * 88) {
-    dp_cols = (int)((tiles / ncu) * ncu / tiles_m);
-    if (!out_f32 && (size_t)M * (size_t)(N - dp_cols * kBN) * sizeof(float) > ws_bytes) dp_cols = tiles_n;
-  }
+  if (ws != nullptr && ws_bytes >= gemm_workspace_bytes() && sk_out_ok && nk >= 64 && rem != 0 && rem * 100 < ncu * 88)
+    dp_cols = (int)((tiles / ncu) * ncu / tiles_m);   // the rest is fewer than ncu tiles
   const int n_dp = dp_cols < tiles_n ? dp_cols * kBN : N;
   if (n_dp > 0) {
     GemmArgs d = g;
@@ -495,13 +511,15 @@ static int launch_bf16_mode(const void* A, const void* B, void* C, const void* b
     GemmArgs r = g;
     r.N = N - n_dp;
     r.B = TB ? g.B + n_dp : g.B + (size_t)n_dp * K;
-    if (out_f32) return launch_sk<TA, TB>(r, (float*)C + n_dp, (size_t)N, ncu, st);
-    const size_t n4 = (size_t)M * r.N / 4;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(256), 0, st, (float4*)ws, n4);
-    const int rc = launch_sk<TA, TB>(r, (float*)ws, (size_t)r.N, ncu, st);
+    const int rc = launch_sk<TA, TB>(r, (float*)ws, ncu, st);
     if (rc != PTDP_OK) return rc;
-    hipLaunchKernelGGL(gemm_sk_convert_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, (const float*)ws,
-                       (bf16_t*)C + n_dp, bias ? (const bf16_t*)bias + n_dp : nullptr, M, r.N, (size_t)N);
+    const int sk_tiles = tiles_m * ((r.N + kBN - 1) / kBN);
+    if (out_f32)
+      hipLaunchKernelGGL(gemm_sk_reduce_kernel<true>, dim3(sk_tiles * 16), dim3(256), 0, st, (const float*)ws,
+                         (void*)((float*)C + n_dp), (const bf16_t*)nullptr, M, r.N, K, (size_t)N, ncu);
+    else
+      hipLaunchKernelGGL(gemm_sk_reduce_kernel<false>, dim3(sk_tiles * 16), dim3(256), 0, st, (const float*)ws,
+                         (void*)((bf16_t*)C + n_dp), bias ? (const bf16_t*)bias + n_dp : nullptr, M, r.N, K, (size_t)N, ncu);
   }
   return PTDP_OK;
 }

@@ -40,7 +40,7 @@ def test_gemm(dtype, mode, M, N, K):
 @pytest.mark.parametrize("M,N,K", [(520, 776, 4168), (264, 4104, 4096), (2048, 1288, 4160), (2048, 10248, 4096)])
 def test_gemm_split_along_k(mode, M, N, K):
     """Tile counts that do not fill the compute units: the remaining tiles are split along k through the
-    fp32 workspace (bf16 output) or straight into the fp32 accumulator."""
+    workspace and reduced in a fixed order (bf16 output, or += into the fp32 accumulator)."""
     dtype = B.BF16
     a = randn((M, K), dtype, 1)
     b = randn((K, N), dtype, 2)
@@ -48,12 +48,18 @@ def test_gemm_split_along_k(mode, M, N, K):
     want = np64(a) @ np64(b)
     A = a.t().contiguous() if mode == B.GEMM_TN else a
     Bm = b.t().contiguous() if mode == B.GEMM_NT else b
-    ws = torch.full((M * N,), 7.0, dtype=torch.float32, device="cuda")      # garbage on entry
+    ws = torch.full((B.ptdp_gemm_workspace_bytes() // 4,), 7.0, dtype=torch.float32, device="cuda")   # garbage on entry
     c = torch.full((M, N), 9.0, dtype=torch.bfloat16, device="cuda")
     B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), c.data_ptr(), bias.data_ptr(), M, N, K, 0, 0,
                         ws.data_ptr(), ws.numel() * 4, stream()), "gemm")
     sync()
     assert_close(np64(c), want + np64(bias), dtype, "C")
+    # bit-reproducible: the partial tiles are summed in a fixed order
+    c1 = torch.empty_like(c)
+    B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), c1.data_ptr(), bias.data_ptr(), M, N, K, 0, 0,
+                        ws.data_ptr(), ws.numel() * 4, stream()), "gemm")
+    sync()
+    assert torch.equal(c, c1)
     # same result as the unsplit path up to bf16 rounding of an fp32 sum taken in another order
     c2 = torch.empty_like(c)
     B.check(B.ptdp_gemm(dtype, mode, A.data_ptr(), Bm.data_ptr(), c2.data_ptr(), bias.data_ptr(), M, N, K, 0, 0,
