@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--recompute", type=int, default=0, metavar="SEG",
+                    help="activation recomputation with a checkpoint every SEG layers (section 3.5); the rerun "
+                         "forward is executed and counted: FLOP factor 4 instead of 3.  Not the default metric.")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="first run a plain 1 GiB read + 1 GiB write kernel (scale reference for FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-sample-positions", type=int, default=0, help="sequence positions of the oracle sample")
@@ -99,6 +102,10 @@ def main():
     yout = [torch.empty_like(xin[0]) for _ in range(n_pairs)]
     din = [torch.empty_like(xin[0]) for _ in range(n_pairs)]
 
+    seg = args.recompute
+    if seg:
+        slot_bytes = chunks[0].checkpoint_bytes(seg)
+        seg_stash = torch.empty(seg * B.ptdp_layer_stash_bytes(C.byref(cfg)), dtype=torch.uint8, device=dev)
     if args.workload == "c5":
         steps = B.schedule_build(w["p"], n_chunks, m, w["rank"])
         n_slots = B.ptdp_schedule_peak_inflight(w["p"], n_chunks, m, w["rank"])
@@ -108,20 +115,31 @@ def main():
         a_in, a_out, a_dout, a_din = arr(xin), arr(yout), arr(dout), arr(din)
 
         def step():
-            B.check(B.ptdp_schedule_run(handles, n_chunks, m, steps, len(steps), a_in, a_out, a_dout, a_din,
-                                        pool.data_ptr(), slot_bytes, n_slots, ws.data_ptr(), sh), "schedule_run")
+            if seg:
+                B.check(B.ptdp_schedule_run_ckpt(handles, n_chunks, m, steps, len(steps), a_in, a_out, a_dout, a_din,
+                                                 pool.data_ptr(), slot_bytes, n_slots, seg, seg_stash.data_ptr(),
+                                                 ws.data_ptr(), sh), "schedule_run_ckpt")
+            else:
+                B.check(B.ptdp_schedule_run(handles, n_chunks, m, steps, len(steps), a_in, a_out, a_dout, a_din,
+                                            pool.data_ptr(), slot_bytes, n_slots, ws.data_ptr(), sh), "schedule_run")
         passes_per_step = n_pairs
     else:
         pool = torch.empty(slot_bytes, dtype=torch.uint8, device=dev)
 
         def step():
-            B.check(chunks[0].forward(0, xin[0].data_ptr(), yout[0].data_ptr(), pool.data_ptr(), ws.data_ptr(), stream),
-                    "chunk_forward")
-            B.check(chunks[0].backward(0, dout[0].data_ptr(), din[0].data_ptr(), pool.data_ptr(), ws.data_ptr(), stream),
-                    "chunk_backward")
+            x, y, dy, dx = xin[0].data_ptr(), yout[0].data_ptr(), dout[0].data_ptr(), din[0].data_ptr()
+            if seg:
+                B.check(chunks[0].forward_ckpt(0, x, y, pool.data_ptr(), seg, seg_stash.data_ptr(), ws.data_ptr(),
+                                               stream), "chunk_forward_ckpt")
+                B.check(chunks[0].backward_ckpt(0, dy, dx, pool.data_ptr(), seg, seg_stash.data_ptr(), ws.data_ptr(),
+                                                stream), "chunk_backward_ckpt")
+            else:
+                B.check(chunks[0].forward(0, x, y, pool.data_ptr(), ws.data_ptr(), stream), "chunk_forward")
+                B.check(chunks[0].backward(0, dy, dx, pool.data_ptr(), ws.data_ptr(), stream), "chunk_backward")
         passes_per_step = 1
 
-    flops_step = 3 * B.ptdp_layer_flops_fwd(C.byref(cfg)) * w["layers"] * passes_per_step
+    flop_factor = 4 if seg else 3
+    flops_step = flop_factor * B.ptdp_layer_flops_fwd(C.byref(cfg)) * w["layers"] * passes_per_step
     torch.cuda.synchronize()
     peak_hbm_bytes = torch.cuda.memory_allocated()
 
@@ -173,13 +191,14 @@ def main():
         cpu = cpu_baseline(w, params[0], args.cpu_sample_positions)
 
     out = {
-        "metric": "model_tflops_per_gpu_fwd_bwd", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "metric": "model_tflops_per_gpu_fwd_bwd" + ("_recompute" if seg else ""), "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "config": {"workload": "%s: %s" % (args.workload, w["desc"]), "h": w["h"], "a": w["a"], "t": w["t"],
                    "s": w["s"], "b": w["b"], "layers": w["layers"], "chunks": n_chunks, "microbatches": m,
-                   "dropout_p": 0.1, "model_flops_per_step": flops_step, "flop_factor": 3,
+                   "dropout_p": 0.1, "model_flops_per_step": flops_step, "flop_factor": flop_factor,
+                   "recompute_segment_layers": seg, "activation_pool_gb": round(pool.numel() / 2 ** 30, 3),
                    "resident_hbm_gb": round(peak_hbm_bytes / 2 ** 30, 2)},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
         "context": "paper: 163 TFLOP/s per A100 = 52% of peak, end-to-end on 3072 GPUs, recompute counted (x4)",

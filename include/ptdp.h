@@ -188,6 +188,28 @@ int ptdp_chunk_forward(ptdp_chunk* chunk, int64_t microbatch, const void* x, voi
 int ptdp_chunk_backward(ptdp_chunk* chunk, int64_t microbatch, const void* dy, void* dx,
                         const void* stash, void* workspace, void* stream);
 
+/* Activation recomputation (section 3.5).  The chunk is cut into segments of
+ * seg_layers consecutive layers (the last may be shorter); only the input
+ * activation of each segment is kept per in-flight microbatch:
+ *   ckpt: dev, ptdp_chunk_n_checkpoints(chunk, seg_layers) * ptdp_checkpoint_bytes
+ *         bytes (written by the forward, read by the backward);
+ *   seg_stash: dev scratch for seg_layers layer stashes, shared by every
+ *         microbatch (garbage between calls).
+ * The backward reruns each segment's forward from its checkpoint (same dropout
+ * masks: they are a pure function of seed, layer, site, microbatch and element
+ * index) and then runs that segment's backward, last segment first.  With c
+ * checkpoints over l layers the kept bytes are c*A_input + (l/c)*A_intermediate
+ * (A_input = ptdp_checkpoint_bytes, A_intermediate = ptdp_layer_stash_bytes).
+ * Results are bit-identical to ptdp_chunk_forward / ptdp_chunk_backward.
+ * seg_layers in [1, n_layers], else PTDP_E_INVALID_ARG. */
+size_t ptdp_checkpoint_bytes(const ptdp_layer_cfg* cfg);
+int ptdp_chunk_n_checkpoints(const ptdp_chunk* chunk, int seg_layers);
+int ptdp_chunk_forward_ckpt(ptdp_chunk* chunk, int64_t microbatch, const void* x, void* y, void* ckpt,
+                            int seg_layers, void* seg_stash, void* workspace, void* stream);
+int ptdp_chunk_backward_ckpt(ptdp_chunk* chunk, int64_t microbatch, const void* dy, void* dx,
+                             const void* ckpt, int seg_layers, void* seg_stash, void* workspace,
+                             void* stream);
+
 /* ---------------------------------------------------------------- schedule */
 
 /* One pass of the device's order: kind 0 = forward, 1 = backward. */
@@ -221,6 +243,15 @@ int ptdp_schedule_run(ptdp_chunk* const* chunks, int v, int m, const ptdp_step* 
                       const void* const* stage_in, void* const* stage_out,
                       const void* const* stage_dout, void* const* stage_din,
                       void* stash_pool, size_t slot_bytes, int n_slots, void* workspace, void* stream);
+
+/* The same with activation recomputation: ckpt_pool holds n_slots checkpoint
+ * sets of slot_bytes each (>= n_checkpoints * ptdp_checkpoint_bytes of every
+ * chunk); seg_stash as in ptdp_chunk_forward_ckpt, one for the whole run. */
+int ptdp_schedule_run_ckpt(ptdp_chunk* const* chunks, int v, int m, const ptdp_step* steps, int n_steps,
+                           const void* const* stage_in, void* const* stage_out,
+                           const void* const* stage_dout, void* const* stage_din,
+                           void* ckpt_pool, size_t slot_bytes, int n_slots, int seg_layers,
+                           void* seg_stash, void* workspace, void* stream);
 
 /* ------------------------------------------------- single kernels (per-op) */
 /* Exported for per-operation parity tests and roofline measurements.  dtype as

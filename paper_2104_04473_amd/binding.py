@@ -82,10 +82,16 @@ SIGNATURES = {
     "ptdp_layer_backward": (_i, [_vp, _i, _i64, _vp, _vp, _vp, _vp, _vp]),
     "ptdp_chunk_forward": (_i, [_vp, _i64, _vp, _vp, _vp, _vp, _vp]),
     "ptdp_chunk_backward": (_i, [_vp, _i64, _vp, _vp, _vp, _vp, _vp]),
+    "ptdp_checkpoint_bytes": (_sz, [_cfgp]),
+    "ptdp_chunk_n_checkpoints": (_i, [_vp, _i]),
+    "ptdp_chunk_forward_ckpt": (_i, [_vp, _i64, _vp, _vp, _vp, _i, _vp, _vp, _vp]),
+    "ptdp_chunk_backward_ckpt": (_i, [_vp, _i64, _vp, _vp, _vp, _i, _vp, _vp, _vp]),
     "ptdp_schedule_build": (_i, [_i, _i, _i, _i, C.POINTER(Step), _i, C.POINTER(_i)]),
     "ptdp_schedule_peak_inflight": (_i, [_i, _i, _i, _i]),
     "ptdp_schedule_run": (_i, [C.POINTER(_vp), _i, _i, C.POINTER(Step), _i, C.POINTER(_vp), C.POINTER(_vp),
                                C.POINTER(_vp), C.POINTER(_vp), _vp, _sz, _i, _vp, _vp]),
+    "ptdp_schedule_run_ckpt": (_i, [C.POINTER(_vp), _i, _i, C.POINTER(Step), _i, C.POINTER(_vp), C.POINTER(_vp),
+                                    C.POINTER(_vp), C.POINTER(_vp), _vp, _sz, _i, _i, _vp, _vp, _vp]),
     "ptdp_layernorm_fwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _f, _vp]),
     "ptdp_layernorm_bwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _vp]),
     "ptdp_bias_gelu_fwd": (_i, [_i, _i, _vp, _vp, _vp, _i, _i, _vp]),
@@ -164,6 +170,17 @@ class Chunk:
 
     def backward(self, mb, dy, dx, stash, ws, stream=None):
         return lib.ptdp_chunk_backward(self.handle, mb, dy, dx, stash, ws, stream_handle(stream))
+
+    def checkpoint_bytes(self, seg_layers):
+        return lib.ptdp_chunk_n_checkpoints(self.handle, seg_layers) * lib.ptdp_checkpoint_bytes(C.byref(self.cfg))
+
+    def forward_ckpt(self, mb, x, y, ckpt, seg_layers, seg_stash, ws, stream=None):
+        return lib.ptdp_chunk_forward_ckpt(self.handle, mb, x, y, ckpt, seg_layers, seg_stash, ws,
+                                           stream_handle(stream))
+
+    def backward_ckpt(self, mb, dy, dx, ckpt, seg_layers, seg_stash, ws, stream=None):
+        return lib.ptdp_chunk_backward_ckpt(self.handle, mb, dy, dx, ckpt, seg_layers, seg_stash, ws,
+                                            stream_handle(stream))
 
     def close(self):
         if self.handle:

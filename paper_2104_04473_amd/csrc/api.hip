@@ -383,6 +383,81 @@ int ptdp_chunk_backward(ptdp_chunk* ch, int64_t microbatch, const void* dy, void
   return PTDP_OK;
 }
 
+// ------------------------------------------------------------------------ activation recomputation
+size_t ptdp_checkpoint_bytes(const ptdp_layer_cfg* cfg) {
+  if (validate(cfg) != PTDP_OK) return 0;
+  const Dims d = dims_of(cfg);
+  const size_t esz = cfg->dtype == PTDP_BF16 ? 2 : 4;
+  return ((size_t)d.T * d.h * esz + 255) / 256 * 256;
+}
+
+int ptdp_chunk_n_checkpoints(const ptdp_chunk* ch, int seg_layers) {
+  if (!ch) return PTDP_E_NULL_PTR;
+  if (seg_layers < 1 || seg_layers > ch->n_layers) return PTDP_E_INVALID_ARG;
+  return (ch->n_layers + seg_layers - 1) / seg_layers;
+}
+
+// Forward of layers [l0, l1) of a chunk with layer l's stash at seg_stash slot (l - l0).  The
+// segment's output goes to `out`.
+static int segment_forward(ptdp_chunk* ch, int l0, int l1, int64_t mb, const void* x, void* out, char* seg_stash,
+                           void* workspace, void* stream) {
+  const void* cur = x;
+  for (int l = l0; l < l1; ++l) {
+    void* y = (l + 1 < l1) ? (void*)(seg_stash + (size_t)(l + 1 - l0) * ch->sl.total + ch->sl.off[PTDP_STASH_X]) : out;
+    PTDP_TRY(ptdp_layer_forward(ch, l, mb, cur, y, seg_stash + (size_t)(l - l0) * ch->sl.total, workspace, stream));
+    cur = y;
+  }
+  return PTDP_OK;
+}
+
+int ptdp_chunk_forward_ckpt(ptdp_chunk* ch, int64_t microbatch, const void* x, void* y, void* ckpt, int seg_layers,
+                            void* seg_stash, void* workspace, void* stream) {
+  if (!ch || !x || !y || !ckpt || !seg_stash || !workspace) return PTDP_E_NULL_PTR;
+  if (microbatch < 0 || x == y || x == ckpt || seg_layers < 1 || seg_layers > ch->n_layers) return PTDP_E_INVALID_ARG;
+  for (int l = 0; l < ch->n_layers; ++l)
+    if (!ch->have_params[l]) return PTDP_E_STATE;
+  const size_t cb = ptdp_checkpoint_bytes(&ch->cfg);
+  const Dims d = dims_of(&ch->cfg);
+  const size_t act = (size_t)d.T * d.h * (ch->cfg.dtype == PTDP_BF16 ? 2 : 4);
+  if (hipMemcpyAsync(ckpt, x, act, hipMemcpyDeviceToDevice, (hipStream_t)stream) != hipSuccess) return PTDP_E_HIP;
+  const int n = ch->n_layers;
+  for (int l0 = 0, sg = 0; l0 < n; l0 += seg_layers, ++sg) {
+    const int l1 = l0 + seg_layers < n ? l0 + seg_layers : n;
+    // a segment's output is the next segment's checkpoint
+    void* out = l1 < n ? (void*)((char*)ckpt + (size_t)(sg + 1) * cb) : y;
+    PTDP_TRY(segment_forward(ch, l0, l1, microbatch, (char*)ckpt + (size_t)sg * cb, out, (char*)seg_stash, workspace,
+                             stream));
+  }
+  return PTDP_OK;
+}
+
+int ptdp_chunk_backward_ckpt(ptdp_chunk* ch, int64_t microbatch, const void* dy, void* dx, const void* ckpt,
+                             int seg_layers, void* seg_stash, void* workspace, void* stream) {
+  if (!ch || !dy || !dx || !ckpt || !seg_stash || !workspace) return PTDP_E_NULL_PTR;
+  if (microbatch < 0 || seg_layers < 1 || seg_layers > ch->n_layers) return PTDP_E_INVALID_ARG;
+  for (int l = 0; l < ch->n_layers; ++l)
+    if (!ch->have_params[l] || !ch->have_grads[l]) return PTDP_E_STATE;
+  const size_t cb = ptdp_checkpoint_bytes(&ch->cfg);
+  const int n = ch->n_layers, n_seg = (n + seg_layers - 1) / seg_layers;
+  char* S = (char*)seg_stash;
+  void* chain = (char*)workspace + ch->wl.off[WS_CHAIN];
+  const void* cur = dy;
+  for (int sg = n_seg - 1; sg >= 0; --sg) {
+    const int l0 = sg * seg_layers, l1 = l0 + seg_layers < n ? l0 + seg_layers : n;
+    // Rerun the segment.  Its output is not needed again: the last segment's goes to the gradient
+    // chain buffer (idle until the first backward), an inner segment's rewrites the next checkpoint
+    // with the bits it already holds.
+    void* out = l1 < n ? (void*)((char*)ckpt + (size_t)(sg + 1) * cb) : chain;
+    PTDP_TRY(segment_forward(ch, l0, l1, microbatch, (const char*)ckpt + (size_t)sg * cb, out, S, workspace, stream));
+    for (int l = l1 - 1; l >= l0; --l) {
+      void* o = l > 0 ? chain : dx;
+      PTDP_TRY(ptdp_layer_backward(ch, l, microbatch, cur, o, S + (size_t)(l - l0) * ch->sl.total, workspace, stream));
+      cur = o;
+    }
+  }
+  return PTDP_OK;
+}
+
 // ------------------------------------------------------------------------------------ schedule
 static int sched_check(int p, int v, int m, int rank) {
   if (p < 1 || v < 1 || m < 1 || rank < 0 || rank >= p) return PTDP_E_INVALID_ARG;
@@ -436,16 +511,25 @@ int ptdp_schedule_peak_inflight(int p, int v, int m, int rank) {
   return w < total ? w + 1 : w;
 }
 
-int ptdp_schedule_run(ptdp_chunk* const* chunks, int v, int m, const ptdp_step* steps, int n_steps,
-                      const void* const* stage_in, void* const* stage_out, const void* const* stage_dout,
-                      void* const* stage_din, void* stash_pool, size_t slot_bytes, int n_slots, void* workspace,
-                      void* stream) {
+// seg_layers == 0: full stashes in the pool; > 0: checkpoints in the pool, seg_stash as scratch.
+static int schedule_run_impl(ptdp_chunk* const* chunks, int v, int m, const ptdp_step* steps, int n_steps,
+                             const void* const* stage_in, void* const* stage_out, const void* const* stage_dout,
+                             void* const* stage_din, void* stash_pool, size_t slot_bytes, int n_slots, int seg_layers,
+                             void* seg_stash, void* workspace, void* stream) {
   if (!chunks || !steps || !stage_in || !stage_out || !stage_dout || !stage_din || !stash_pool || !workspace)
     return PTDP_E_NULL_PTR;
+  if (seg_layers > 0 && !seg_stash) return PTDP_E_NULL_PTR;
   if (v < 1 || m < 1 || n_steps < 0 || n_slots < 0) return PTDP_E_INVALID_ARG;
   for (int c = 0; c < v; ++c) {
     if (!chunks[c]) return PTDP_E_NULL_PTR;
-    if (slot_bytes < (size_t)chunks[c]->n_layers * chunks[c]->sl.total) return PTDP_E_TOO_SMALL;
+    if (seg_layers > 0) {
+      const int nc = ptdp_chunk_n_checkpoints(chunks[c], seg_layers);
+      if (nc < 0) return nc;
+      if (slot_bytes < (size_t)nc * ptdp_checkpoint_bytes(&chunks[c]->cfg)) return PTDP_E_TOO_SMALL;
+      if (chunks[c]->sl.total > chunks[0]->sl.total) return PTDP_E_INVALID_ARG;  // one seg_stash serves all
+    } else if (slot_bytes < (size_t)chunks[c]->n_layers * chunks[c]->sl.total) {
+      return PTDP_E_TOO_SMALL;
+    }
     if (ws_layout(&chunks[c]->cfg).total > ws_layout(&chunks[0]->cfg).total) return PTDP_E_INVALID_ARG;
   }
   // dry run on the host: slot assignment, order validity, capacity
@@ -476,13 +560,38 @@ int ptdp_schedule_run(ptdp_chunk* const* chunks, int v, int m, const ptdp_step* 
     const ptdp_step& s = steps[i];
     const size_t id = (size_t)s.chunk * m + s.microbatch;
     char* slot = (char*)stash_pool + (size_t)assigned[i] * slot_bytes;
-    if (s.kind == 0)
-      PTDP_TRY(ptdp_chunk_forward(chunks[s.chunk], s.microbatch, stage_in[id], stage_out[id], slot, workspace, stream));
-    else
-      PTDP_TRY(ptdp_chunk_backward(chunks[s.chunk], s.microbatch, stage_dout[id], stage_din[id], slot, workspace,
-                                   stream));
+    ptdp_chunk* ch = chunks[s.chunk];
+    if (seg_layers > 0) {
+      if (s.kind == 0)
+        PTDP_TRY(ptdp_chunk_forward_ckpt(ch, s.microbatch, stage_in[id], stage_out[id], slot, seg_layers, seg_stash,
+                                         workspace, stream));
+      else
+        PTDP_TRY(ptdp_chunk_backward_ckpt(ch, s.microbatch, stage_dout[id], stage_din[id], slot, seg_layers,
+                                          seg_stash, workspace, stream));
+    } else if (s.kind == 0) {
+      PTDP_TRY(ptdp_chunk_forward(ch, s.microbatch, stage_in[id], stage_out[id], slot, workspace, stream));
+    } else {
+      PTDP_TRY(ptdp_chunk_backward(ch, s.microbatch, stage_dout[id], stage_din[id], slot, workspace, stream));
+    }
   }
   return PTDP_OK;
+}
+
+int ptdp_schedule_run(ptdp_chunk* const* chunks, int v, int m, const ptdp_step* steps, int n_steps,
+                      const void* const* stage_in, void* const* stage_out, const void* const* stage_dout,
+                      void* const* stage_din, void* stash_pool, size_t slot_bytes, int n_slots, void* workspace,
+                      void* stream) {
+  return schedule_run_impl(chunks, v, m, steps, n_steps, stage_in, stage_out, stage_dout, stage_din, stash_pool,
+                           slot_bytes, n_slots, 0, nullptr, workspace, stream);
+}
+
+int ptdp_schedule_run_ckpt(ptdp_chunk* const* chunks, int v, int m, const ptdp_step* steps, int n_steps,
+                           const void* const* stage_in, void* const* stage_out, const void* const* stage_dout,
+                           void* const* stage_din, void* ckpt_pool, size_t slot_bytes, int n_slots, int seg_layers,
+                           void* seg_stash, void* workspace, void* stream) {
+  if (seg_layers < 1) return PTDP_E_INVALID_ARG;
+  return schedule_run_impl(chunks, v, m, steps, n_steps, stage_in, stage_out, stage_dout, stage_din, ckpt_pool,
+                           slot_bytes, n_slots, seg_layers, seg_stash, workspace, stream);
 }
 
 // ------------------------------------------------------------------------- single-kernel exports
