@@ -119,7 +119,7 @@ enum {
 
 /* Checks a configuration: struct_size, h % a == 0, a % t == 0, (4h) % t == 0,
  * dh % 8 == 0, sizes > 0, 0 <= p_hidden < 1, ln_eps > 0, causal == 1, known
- * dtype / gelu_mode.  bf16 needs dh in {64, 128, 160} for the MFMA attention
+ * dtype / gelu_mode.  bf16 needs dh in {32, 64, 96, 128, 160} for the MFMA attention
  * kernels, otherwise PTDP_E_UNSUPPORTED. */
 int ptdp_cfg_validate(const ptdp_layer_cfg* cfg);
 
@@ -136,6 +136,15 @@ size_t ptdp_workspace_bytes(const ptdp_layer_cfg* cfg);
  * (24 b s h^2 + 4 b s^2 h) / t  (paper appendix; GEMMs only, full s x s
  * attention matrix).  Backward is counted as twice this.  -1 on invalid cfg. */
 int64_t ptdp_layer_flops_fwd(const ptdp_layer_cfg* cfg);
+
+/* Time to process one batch on a p-stage pipeline without interleaving,
+ * ignoring communication (section 3.4, eq. (1)): a data-parallel replica's
+ * share b_prime = B/d of the batch is cut into b_prime/b microbatches of size
+ * b, each costing t_fwd + t_bwd per stage, plus p - 1 bubble slots:
+ *   (b_prime / b + p - 1) * (t_fwd + t_bwd).
+ * Host-only.  NaN unless b_prime, b, p >= 1, b divides b_prime and both times
+ * are finite and >= 0. */
+double ptdp_batch_time(int64_t b_prime, int64_t b, int p, double t_fwd, double t_bwd);
 
 /* The 64-bit word of the dropout stream that serves elements 4*group ..
  * 4*group+3 of dropout site `site` (0 after attention, 1 after the MLP) of

@@ -45,3 +45,10 @@ def iteration_flops(B, s, l, h, V):
 
 def training_days(T_tokens, P, n, X):
     return 8.0 * T_tokens * P / (n * X) / 86400.0
+
+
+def batch_time(b_prime, b, p, t_f, t_b):
+    """Eq. (1), section 3.4: b_prime/b microbatches through p stages cost
+    (b_prime/b + p - 1) slots of one forward plus one backward each."""
+    assert b_prime % b == 0
+    return (b_prime // b + p - 1) * (t_f + t_b)

@@ -72,6 +72,7 @@ SIGNATURES = {
     "ptdp_stash_offset": (_sz, [_cfgp, _i]),
     "ptdp_workspace_bytes": (_sz, [_cfgp]),
     "ptdp_layer_flops_fwd": (_i64, [_cfgp]),
+    "ptdp_batch_time": (C.c_double, [_i64, _i64, _i, C.c_double, C.c_double]),
     "ptdp_hash": (_u64, [_u64, _u32, _u32, _u64, _u64]),
     "ptdp_chunk_create": (_i, [_cfgp, _i, _i, C.POINTER(_vp)]),
     "ptdp_chunk_destroy": (None, [_vp]),

@@ -1,6 +1,7 @@
 // Host side of libptdp: argument checks, stash / workspace layout, layer and chunk composition,
 // pipeline order of one device, profiling.  Every exported function is declared in include/ptdp.h.
 #include <new>
+#include <cmath>
 #include <vector>
 
 #include "common.h"
@@ -204,6 +205,13 @@ int64_t ptdp_layer_flops_fwd(const ptdp_layer_cfg* cfg) {
   if (validate(cfg) != PTDP_OK) return -1;
   const int64_t b = cfg->b, s = cfg->s, h = cfg->h;
   return (24 * b * s * h * h + 4 * b * s * s * h) / cfg->t;
+}
+
+double ptdp_batch_time(int64_t b_prime, int64_t b, int p, double t_fwd, double t_bwd) {
+  if (b_prime < 1 || b < 1 || p < 1 || b_prime % b != 0 || !(t_fwd >= 0.0) || !(t_bwd >= 0.0) || std::isinf(t_fwd) ||
+      std::isinf(t_bwd))
+    return std::nan("");
+  return (double)(b_prime / b + p - 1) * (t_fwd + t_bwd);
 }
 
 uint64_t ptdp_hash(uint64_t seed, uint32_t layer, uint32_t site, uint64_t microbatch, uint64_t group) {

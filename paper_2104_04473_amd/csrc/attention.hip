@@ -612,7 +612,7 @@ attn_delta_bf16(const bf16_t* __restrict__ ctx, const bf16_t* __restrict__ dctx,
 bool attn_dh_supported(int dtype, int dh) {
   if (dh <= 0 || dh % 8 != 0) return false;
   if (dtype == PTDP_F32) return dh <= 64 * kMaxDimsPerLane;
-  return dh == 64 || dh == 128 || dh == 160;
+  return dh == 32 || dh == 64 || dh == 96 || dh == 128 || dh == 160;
 }
 
 static inline double attn_flops(int s, int b, int heads, int dh) { return 4.0 * b * heads * (double)s * s * dh; }
@@ -644,7 +644,9 @@ int launch_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, in
   } else {
     const bf16_t* q = (const bf16_t*)qkv;
     bf16_t* c = (bf16_t*)ctx;
-    if (dh == 64) rc = attn_fwd_mfma_t<64>(q, c, lse, s, b, heads, stream);
+    if (dh == 32) rc = attn_fwd_mfma_t<32>(q, c, lse, s, b, heads, stream);
+    else if (dh == 96) rc = attn_fwd_mfma_t<96>(q, c, lse, s, b, heads, stream);
+    else if (dh == 64) rc = attn_fwd_mfma_t<64>(q, c, lse, s, b, heads, stream);
     else if (dh == 128) rc = attn_fwd_mfma_t<128>(q, c, lse, s, b, heads, stream);
     else rc = attn_fwd_mfma_t<160>(q, c, lse, s, b, heads, stream);
   }
@@ -701,7 +703,9 @@ int launch_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* ls
     const bf16_t* c = (const bf16_t*)ctx;
     const bf16_t* d = (const bf16_t*)dctx;
     bf16_t* o = (bf16_t*)dqkv;
-    if (dh == 64) rc = attn_bwd_mfma_t<64>(q, c, lse, d, o, delta, s, b, heads, stream);
+    if (dh == 32) rc = attn_bwd_mfma_t<32>(q, c, lse, d, o, delta, s, b, heads, stream);
+    else if (dh == 96) rc = attn_bwd_mfma_t<96>(q, c, lse, d, o, delta, s, b, heads, stream);
+    else if (dh == 64) rc = attn_bwd_mfma_t<64>(q, c, lse, d, o, delta, s, b, heads, stream);
     else if (dh == 128) rc = attn_bwd_mfma_t<128>(q, c, lse, d, o, delta, s, b, heads, stream);
     else rc = attn_bwd_mfma_t<160>(q, c, lse, d, o, delta, s, b, heads, stream);
   }

@@ -267,19 +267,21 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[kBM / WGM / 
   const int c4 = (lane & 15) * 4;            // first of this lane's 4 columns inside the wave's 64
   const int n = n0 + wn0 + c4;
   typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+  // Gradient accumulators are touched once per launch: stream them past the caches.  The old values of
+  // slab i + 1 are requested before slab i is staged and added, so two slabs of loads are in flight.
+  f32x4_t old[2][8];
+  auto fetch_old = [&](int i, f32x4_t (&dst)[8]) {
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int m = m0 + wm0 + i * 32 + it * 4 + (lane >> 4);
+      if (m < M && n < N)
+        dst[it] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n));
+    }
+  };
+  if (OUT == OUT_F32_RMW) fetch_old(0, old[0]);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    // gradient accumulators are touched once per launch: stream them past the caches, and ask for the
-    // whole slab before the staging traffic so that the loads overlap it
-    f32x4_t old[8];
-    if (OUT == OUT_F32_RMW) {
-#pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int m = m0 + wm0 + i * 32 + it * 4 + (lane >> 4);
-        if (m < M && n < N)
-          old[it] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n));
-      }
-    }
+    if (OUT == OUT_F32_RMW && i + 1 < TM) fetch_old(i + 1, old[(i + 1) & 1]);
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -298,7 +300,7 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[kBM / WGM / 
           o.y = pack_bf16x2(v.z, v.w);
           *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + (size_t)m * ldc + n) = o;
         } else if (OUT == OUT_F32_RMW) {
-          f32x4_t o = old[it];
+          f32x4_t o = old[i & 1][it];
           o[0] += v.x; o[1] += v.y; o[2] += v.z; o[3] += v.w;
           __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n));
         } else {

@@ -148,3 +148,13 @@ def test_single_kernel_argument_checks():
     assert B.ptdp_attn_fwd(B.F32, None, 256, 256, 16, 1, 1, 64, None) == B.E_NULL_PTR
     assert B.ptdp_dropout_mask(None, 16, 0.1, 0, 0, 0, 0, None) == B.E_NULL_PTR
     assert B.ptdp_colsum_scratch_bytes(2048, 25600) >= 64 * 25600 * 4
+
+
+def test_batch_time_matches_oracle_and_rejects_bad_input():
+    import math
+    from oracle import flops as F
+    for bp, b, p, tf, tb in [(128, 4, 8, 0.013, 0.027), (512, 1, 8, 1.0, 2.0), (12, 3, 1, 0.5, 1.5), (8, 8, 64, 2.0, 0.0)]:
+        assert B.ptdp_batch_time(bp, b, p, tf, tb) == F.batch_time(bp, b, p, tf, tb)
+    for bad in [(0, 1, 1, 1.0, 1.0), (8, 3, 2, 1.0, 1.0), (8, 2, 0, 1.0, 1.0), (8, 2, 2, -1.0, 1.0),
+                (8, 2, 2, float("nan"), 1.0), (8, 2, 2, 1.0, float("inf"))]:
+        assert math.isnan(B.ptdp_batch_time(*bad))

@@ -53,3 +53,24 @@ def test_shard_flops():
     assert F.shard_layer_flops(1, 2048, 12288, 8) == 3 * 953482739712
     assert F.shard_layer_flops(2, 128, 256, 1) == 1308622848
     assert F.shard_layer_flops(1, 2048, 12288, 8, recompute=True) == 4 * 953482739712
+
+
+def test_eq1_is_the_makespan_of_the_simulated_pipeline():
+    """Eq. (1) against the p-device simulation of the non-interleaved schedule (an independent
+    computation: event-driven dependencies, no closed form)."""
+    from oracle import schedule as S
+    for p, m, tf, tb in [(4, 8, 1.0, 2.0), (8, 16, 0.7, 1.9), (1, 5, 1.0, 1.0), (3, 3, 2.0, 3.5)]:
+        makespan, _ = S.simulate(p, 1, m, t_f=tf, t_b=tb)
+        assert abs(makespan - F.batch_time(m * 4, 4, p, tf, tb)) < 1e-9
+
+
+def test_eq1_limits():
+    # cost proportional to b (no fixed overhead): the smallest microbatch wins (fewest bubble samples)
+    times = {b: F.batch_time(64, b, 8, 1.0 * b, 2.0 * b) for b in (1, 2, 4, 8)}
+    assert min(times, key=times.get) == 1
+    assert times[1] == (64 + 7) * 3.0
+    # cost independent of b (pure overhead): the largest microbatch wins
+    times = {b: F.batch_time(64, b, 8, 1.0, 2.0) for b in (1, 2, 4, 8)}
+    assert min(times, key=times.get) == 8
+    # p = 1: no bubble, time = (b'/b) (t_f + t_b)
+    assert F.batch_time(12, 3, 1, 0.5, 1.5) == 4 * 2.0
