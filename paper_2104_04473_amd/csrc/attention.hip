@@ -225,6 +225,38 @@ template <int DH> struct TileRegs {
   }
 };
 
+// This thread's chunk positions inside a tile, computed once: element offsets for the loads (rows rs
+// apart) and byte offsets for the LDS stores.  A tile that lies wholly inside the sequence is then
+// loaded with one add per chunk; the last, ragged tile takes TileRegs::load.
+template <int DH> struct TileMap {
+  uint32_t src[TileGeom<DH>::NCH];
+  uint32_t dst[TileGeom<DH>::NCH];
+  __device__ __forceinline__ void init(size_t rs) {
+#pragma unroll
+    for (int i = 0; i < TileGeom<DH>::NCH; ++i) {
+      const int c = threadIdx.x + i * kAttnThreads;
+      const int row = c / (DH / 8), ch = c % (DH / 8);
+      src[i] = (uint32_t)(row * rs + ch * 8);
+      dst[i] = (uint32_t)(row * TileGeom<DH>::STRIDE + ch * 16);
+    }
+  }
+  // rows row0 .. row0+63 of src (row pitch rs); s = number of valid rows
+  __device__ __forceinline__ void load(TileRegs<DH>& t, const bf16_t* __restrict__ src_base, size_t rs, int row0,
+                                       int s) const {
+    if (row0 + kBKV <= s) {
+      const bf16_t* p = src_base + (size_t)row0 * rs;
+#pragma unroll
+      for (int i = 0; i < TileGeom<DH>::NCH; ++i) t.v[i] = *reinterpret_cast<const uint4*>(p + src[i]);
+    } else {
+      t.load(src_base, rs, row0, s);
+    }
+  }
+  __device__ __forceinline__ void store(const TileRegs<DH>& t, char* lds) const {
+#pragma unroll
+    for (int i = 0; i < TileGeom<DH>::NCH; ++i) *reinterpret_cast<uint4*>(lds + dst[i]) = t.v[i];
+  }
+};
+
 // MFMA fragment with the tile row as the MFMA row: row = sub*32 + (lane & 31), eight consecutive dh of k16 step kk.
 template <int DH>
 __device__ __forceinline__ bf16x8_t frag_direct(const char* lds, int sub, int kk, int l31, int half) {
@@ -295,11 +327,14 @@ __device__ __forceinline__ bool attn_map(int id, int nblk, int heads, int b, int
 inline int attn_grid(int nblk, int heads, int b) { return 8 * ((heads * b + 7) / 8) * nblk; }
 
 // Forward: S^T = K Q^T and O^T = V^T P^T, so that the probabilities leave the first MFMA in the register
-// layout the second one takes as its B operand.  Tiles pass through few registers on purpose: two or
-// three workgroups share a CU and hide each other's load latency, which needs the register budget
-// more than a software prefetch does.
+// layout the second one takes as its B operand.  One tile's worth of registers carries V of the
+// current step (requested before the score MFMAs, stored to LDS after the softmax) and then K of the
+// next step (requested before the P V MFMAs), so both loads overlap arithmetic.  The loop is bound by
+// vector ALU work, not by MFMA: the output is rescaled only when some row's running maximum moved,
+// the mask is applied only on tiles that touch the diagonal, and exponentials and bf16 conversions
+// are single instructions.
 template <int DH>
-__global__ void __launch_bounds__(kAttnThreads, 2)
+__global__ void __launch_bounds__(kAttnThreads, DH > 128 ? 1 : 2)
 attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* __restrict__ lse, int s, int b,
               int heads) {
   constexpr int NKK = DH / 16, NDT = DH / 32;
@@ -330,63 +365,79 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
 
   const int q_last_blk = min(s, (qblk + 1) * kBQ) - 1;
   const int ntiles = q_last_blk / kBKV + 1;
-  TileRegs<DH> kr;
+  TileMap<DH> map;
+  map.init(rs);
+  TileRegs<DH> tr;
+  map.load(tr, base + hp, rs, 0, s);
+  map.store(tr, k_lds);
+  __syncthreads();
   for (int kt = 0; kt < ntiles; ++kt) {
     const int key0 = kt * kBKV;
-    __syncthreads();
-    kr.load(base + hp, rs, key0, s);
-    kr.store(k_lds);
-    kr.load(base + 2 * hp, rs, key0, s);
-    kr.store(v_lds);
-    __syncthreads();
-    if (key0 > q_first + 31) continue;  // every key of the tile is in this wave's future
+    const bool active = key0 <= q_first + 31;  // else every key of the tile is in this wave's future
+    map.load(tr, base + 2 * hp, rs, key0, s);
 
-    f32x16_t sacc[2];
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      sacc[sub] = zero16();
-#pragma unroll
-      for (int kk = 0; kk < NKK; ++kk)
-        sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(k_lds, sub, kk, l31, half), qf[kk],
-                                                            sacc[sub], 0, 0, 0);
-    }
-    // causal mask (also hides keys >= s, which are > every valid query) and running max
-    const bool need_mask = key0 + kBKV - 1 > q_first;
-    float mx = m_run;
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        if (need_mask && key > my_q) sacc[sub][r] = -INFINITY;
-        mx = fmaxf(mx, sacc[sub][r]);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float corr = exp2f((m_run - mx) * c2);
-    m_run = mx;
-    l_run *= corr;
-#pragma unroll
-    for (int d = 0; d < NDT; ++d)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[d][r] *= corr;
     bf16x8_t pf[2][2];
+    if (active) {
+      f32x16_t sacc[2];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+      for (int sub = 0; sub < 2; ++sub) {
+        sacc[sub] = zero16();
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        sacc[sub][r] = exp2f((sacc[sub][r] - mx) * c2);
-        l_run += sacc[sub][r];
+        for (int kk = 0; kk < NKK; ++kk)
+          sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(k_lds, sub, kk, l31, half), qf[kk],
+                                                              sacc[sub], 0, 0, 0);
       }
-      pf[sub][0] = pack_frag(sacc[sub], 0);
-      pf[sub][1] = pack_frag(sacc[sub], 1);
-    }
+      // causal mask (also hides keys >= s, which are > every valid query); only tiles on the diagonal need it
+      if (key0 + kBKV - 1 > q_first) {
 #pragma unroll
-    for (int d = 0; d < NDT; ++d)
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            sacc[sub][r] = key > my_q ? -INFINITY : sacc[sub][r];
+          }
+      }
+      float mx = m_run;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(v_lds, d, sub, ks, lane), pf[sub][ks], o[d], 0, 0, 0);
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[sub][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      if (__any(mx > m_run)) {   // some row's maximum moved: rescale what has been accumulated
+        const float corr = __builtin_amdgcn_exp2f((m_run - mx) * c2);
+        m_run = mx;
+        l_run *= corr;
+#pragma unroll
+        for (int d = 0; d < NDT; ++d)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[d][r] *= corr;
+      }
+      const float mc = mx * c2;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          sacc[sub][r] = __builtin_amdgcn_exp2f(sacc[sub][r] * c2 - mc);
+          l_run += sacc[sub][r];
+        }
+        pf[sub][0] = pack_frag(sacc[sub], 0);
+        pf[sub][1] = pack_frag(sacc[sub], 1);
+      }
+    }
+    map.store(tr, v_lds);
+    __syncthreads();   // V visible; every wave is done with K of this step
+    if (kt + 1 < ntiles) map.load(tr, base + hp, rs, key0 + kBKV, s);
+    if (active) {
+#pragma unroll
+      for (int d = 0; d < NDT; ++d)
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks)
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(v_lds, d, sub, ks, lane), pf[sub][ks], o[d], 0, 0, 0);
+    }
+    if (kt + 1 < ntiles) map.store(tr, k_lds);
+    __syncthreads();   // next K visible; every wave is done with V of this step
   }
   l_run += __shfl_xor(l_run, 32, 64);
   if (my_q < s) {
@@ -401,7 +452,7 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
 //   dP = dO V^T, dS = P o (dP - delta), dQ = dS K / sqrt(dh), dK = dS^T Q / sqrt(dh), dV = P^T dO
 // ------------------------------------------------------------------------------------------------
 template <int DH>
-__global__ void __launch_bounds__(kAttnThreads, 2)
+__global__ void __launch_bounds__(kAttnThreads, DH >= 96 ? 1 : 2)
 attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
                  const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads) {
   constexpr int NKK = DH / 16, NDT = DH / 32;
@@ -438,16 +489,24 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
 
   const int q_last_blk = min(s, (qblk + 1) * kBQ) - 1;
   const int ntiles = q_last_blk / kBKV + 1;
-  TileRegs<DH> kr;
+  // the next K and V tiles travel in registers while this step's arithmetic runs
+  TileMap<DH> map;
+  map.init(rs);
+  TileRegs<DH> kr, vr;
+  map.load(kr, base + hp, rs, 0, s);
+  map.load(vr, base + 2 * hp, rs, 0, s);
   for (int kt = 0; kt < ntiles; ++kt) {
     const int key0 = kt * kBKV;
     __syncthreads();
-    kr.load(base + hp, rs, key0, s);
-    kr.store(k_lds);
-    kr.load(base + 2 * hp, rs, key0, s);
-    kr.store(v_lds);
+    map.store(kr, k_lds);
+    map.store(vr, v_lds);
     __syncthreads();
+    if (kt + 1 < ntiles) {
+      map.load(kr, base + hp, rs, key0 + kBKV, s);
+      map.load(vr, base + 2 * hp, rs, key0 + kBKV, s);
+    }
     if (key0 > q_first + 31) continue;
+    const bool diag = key0 + kBKV - 1 > q_first;   // only tiles on the diagonal need the mask
     bf16x8_t dsf[2][2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -457,11 +516,16 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(k_lds, sub, kk, l31, half), qf[kk], sacc, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(v_lds, sub, kk, l31, half), dof[kk], dp, 0, 0, 0);
       }
+      if (diag) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        const float p = key > my_q ? 0.f : exp2f(sacc[r] * c2 - L2);
-        sacc[r] = p * (dp[r] - D);
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+          const float p = __builtin_amdgcn_exp2f(sacc[r] * c2 - L2);
+          sacc[r] = key > my_q ? 0.f : p * (dp[r] - D);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = __builtin_amdgcn_exp2f(sacc[r] * c2 - L2) * (dp[r] - D);
       }
       dsf[sub][0] = pack_frag(sacc, 0);
       dsf[sub][1] = pack_frag(sacc, 1);
@@ -516,23 +580,55 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
     dv[d] = zero16();
   }
   const int nq_tiles = (s + kBKV - 1) / kBKV;
-  for (int qt = (kblk * kBQ) / kBKV; qt < nq_tiles; ++qt) {
+  // the next Q and dO tiles (and their lse, delta) travel in registers while this step's arithmetic runs
+  // (not for the largest head size: the tiles would not fit the register file next to dK and dV)
+  constexpr bool kPrefetch = DH <= 128;
+  TileMap<kPrefetch ? DH : 32> qmap, domap;
+  TileRegs<kPrefetch ? DH : 32> qr, dor;
+  float lse_r = 0.f, delta_r = 0.f;
+  auto fetch = [&](int q0) {
+    if constexpr (kPrefetch) {
+      qmap.load(qr, base, rs, q0, s);
+      domap.load(dor, dobase, dors, q0, s);
+      if (threadIdx.x < kBKV) {
+        const int q = q0 + threadIdx.x;
+        lse_r = q < s ? lse_h[q] * 1.4426950408889634f : INFINITY;
+        delta_r = q < s ? delta_h[q] : 0.f;
+      }
+    }
+  };
+  const int qt_first = (kblk * kBQ) / kBKV;
+  if constexpr (kPrefetch) {
+    qmap.init(rs);
+    domap.init(dors);
+    fetch(qt_first * kBKV);
+  }
+  for (int qt = qt_first; qt < nq_tiles; ++qt) {
     const int q0 = qt * kBKV;
     __syncthreads();
-    {
+    if constexpr (kPrefetch) {
+      qmap.store(qr, q_lds);
+      domap.store(dor, do_lds);
+      if (threadIdx.x < kBKV) {
+        lse_lds[threadIdx.x] = lse_r;
+        delta_lds[threadIdx.x] = delta_r;
+      }
+    } else {
       TileRegs<DH> t;
       t.load(base, rs, q0, s);
       t.store(q_lds);
       t.load(dobase, dors, q0, s);
       t.store(do_lds);
-    }
-    if (threadIdx.x < kBKV) {
-      const int q = q0 + threadIdx.x;
-      lse_lds[threadIdx.x] = q < s ? lse_h[q] * 1.4426950408889634f : INFINITY;
-      delta_lds[threadIdx.x] = q < s ? delta_h[q] : 0.f;
+      if (threadIdx.x < kBKV) {
+        const int q = q0 + threadIdx.x;
+        lse_lds[threadIdx.x] = q < s ? lse_h[q] * 1.4426950408889634f : INFINITY;
+        delta_lds[threadIdx.x] = q < s ? delta_h[q] : 0.f;
+      }
     }
     __syncthreads();
+    if (qt + 1 < nq_tiles) fetch(q0 + kBKV);
     if (q0 + kBKV - 1 < key_first) continue;  // every query of the tile precedes this wave's keys
+    const bool diag = q0 < key_first + 32;    // some query of the tile precedes some key of this wave
     bf16x8_t pf[2][2], dsf[2][2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -551,7 +647,8 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int r = 4 * g + i;
-          const float p = my_key > q0 + ql + i ? 0.f : exp2f(sacc[r] * c2 - Ls[i]);
+          float p = __builtin_amdgcn_exp2f(sacc[r] * c2 - Ls[i]);   // lse = +inf past the end gives 0
+          if (diag) p = my_key > q0 + ql + i ? 0.f : p;
           sacc[r] = p;
           dp[r] = p * (dp[r] - Ds[i]);
         }
