@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--recompute", type=int, default=0, metavar="SEG",
                     help="activation recomputation with a checkpoint every SEG layers (section 3.5); the rerun "
                          "forward is executed and counted: FLOP factor 4 instead of 3.  Not the default metric.")
+    ap.add_argument("--stage", default="middle", choices=["middle", "first", "last"],
+                    help="first: embedding forward/backward around the layers; last: final LayerNorm, logit layer "
+                         "(V=51200 split over t) and loss after them.  Not the default metric.")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="first run a plain 1 GiB read + 1 GiB write kernel (scale reference for FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-sample-positions", type=int, default=0, help="sequence positions of the oracle sample")
@@ -106,6 +109,9 @@ def main():
     if seg:
         slot_bytes = chunks[0].checkpoint_bytes(seg)
         seg_stash = torch.empty(seg * B.ptdp_layer_stash_bytes(C.byref(cfg)), dtype=torch.uint8, device=dev)
+    if args.workload == "c5" and (args.stage != "middle"):
+        print("bench.py: --stage first/last is measured on the single-chunk workloads", file=sys.stderr)
+        sys.exit(2)
     if args.workload == "c5":
         steps = B.schedule_build(w["p"], n_chunks, m, w["rank"])
         n_slots = B.ptdp_schedule_peak_inflight(w["p"], n_chunks, m, w["rank"])
@@ -126,20 +132,53 @@ def main():
     else:
         pool = torch.empty(slot_bytes, dtype=torch.uint8, device=dev)
 
+        V = 51200
+        vrows = V // w["t"]
+        if args.stage != "middle":
+            lm_ws = torch.empty(B.ptdp_lm_workspace_bytes(C.byref(cfg), vrows), dtype=torch.uint8, device=dev)
+            e_word = (0.02 * torch.randn((vrows, w["h"]), device=dev)).to(torch.bfloat16)
+            e_pos = (0.02 * torch.randn((w["s"], w["h"]), device=dev)).to(torch.bfloat16)
+            d_e_word = torch.zeros((vrows, w["h"]), dtype=torch.float32, device=dev)
+            d_e_pos = torch.zeros((w["s"], w["h"]), dtype=torch.float32, device=dev)
+            gen = torch.Generator(device="cpu"); gen.manual_seed(7)
+            ids = torch.randint(0, V, (w["s"], w["b"]), generator=gen, dtype=torch.int32).to(dev)
+            lnf_g = torch.ones(w["h"], dtype=torch.bfloat16, device=dev); lnf_b = torch.zeros_like(lnf_g)
+            d_lnf_g = torch.zeros(w["h"], dtype=torch.float32, device=dev); d_lnf_b = torch.zeros_like(d_lnf_g)
+            loss = torch.zeros(1, dtype=torch.float32, device=dev)
+            token_loss = torch.zeros(w["s"] * w["b"], dtype=torch.float32, device=dev)
+
         def step():
             x, y, dy, dx = xin[0].data_ptr(), yout[0].data_ptr(), dout[0].data_ptr(), din[0].data_ptr()
+            if args.stage == "first":
+                B.check(B.ptdp_embedding_forward(C.byref(cfg), 0, vrows, ids.data_ptr(), e_word.data_ptr(),
+                                                 e_pos.data_ptr(), x, 0, sh), "embedding_forward")
             if seg:
                 B.check(chunks[0].forward_ckpt(0, x, y, pool.data_ptr(), seg, seg_stash.data_ptr(), ws.data_ptr(),
                                                stream), "chunk_forward_ckpt")
+                if args.stage == "last":
+                    B.check(B.ptdp_lm_head_step(C.byref(cfg), 0, vrows, y, lnf_g.data_ptr(), lnf_b.data_ptr(),
+                                                e_word.data_ptr(), ids.data_ptr(), 1.0, loss.data_ptr(),
+                                                token_loss.data_ptr(), dy, d_lnf_g.data_ptr(), d_lnf_b.data_ptr(),
+                                                d_e_word.data_ptr(), lm_ws.data_ptr(), sh), "lm_head_step")
                 B.check(chunks[0].backward_ckpt(0, dy, dx, pool.data_ptr(), seg, seg_stash.data_ptr(), ws.data_ptr(),
                                                 stream), "chunk_backward_ckpt")
             else:
                 B.check(chunks[0].forward(0, x, y, pool.data_ptr(), ws.data_ptr(), stream), "chunk_forward")
+                if args.stage == "last":
+                    B.check(B.ptdp_lm_head_step(C.byref(cfg), 0, vrows, y, lnf_g.data_ptr(), lnf_b.data_ptr(),
+                                                e_word.data_ptr(), ids.data_ptr(), 1.0, loss.data_ptr(),
+                                                token_loss.data_ptr(), dy, d_lnf_g.data_ptr(), d_lnf_b.data_ptr(),
+                                                d_e_word.data_ptr(), lm_ws.data_ptr(), sh), "lm_head_step")
                 B.check(chunks[0].backward(0, dy, dx, pool.data_ptr(), ws.data_ptr(), stream), "chunk_backward")
+            if args.stage == "first":
+                B.check(B.ptdp_embedding_backward(C.byref(cfg), 0, vrows, ids.data_ptr(), dx, d_e_word.data_ptr(),
+                                                  d_e_pos.data_ptr(), lm_ws.data_ptr(), 0, sh), "embedding_backward")
         passes_per_step = 1
 
     flop_factor = 4 if seg else 3
     flops_step = flop_factor * B.ptdp_layer_flops_fwd(C.byref(cfg)) * w["layers"] * passes_per_step
+    if args.stage == "last":
+        flops_step += 3 * B.ptdp_logit_flops_fwd(C.byref(cfg), 51200 // w["t"])      # 6 b s h V / t
     torch.cuda.synchronize()
     peak_hbm_bytes = torch.cuda.memory_allocated()
 
@@ -191,14 +230,14 @@ def main():
         cpu = cpu_baseline(w, params[0], args.cpu_sample_positions)
 
     out = {
-        "metric": "model_tflops_per_gpu_fwd_bwd" + ("_recompute" if seg else ""), "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "metric": "model_tflops_per_gpu_fwd_bwd" + ("_recompute" if seg else "") + ("" if args.stage == "middle" else "_%s_stage" % args.stage), "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "config": {"workload": "%s: %s" % (args.workload, w["desc"]), "h": w["h"], "a": w["a"], "t": w["t"],
                    "s": w["s"], "b": w["b"], "layers": w["layers"], "chunks": n_chunks, "microbatches": m,
                    "dropout_p": 0.1, "model_flops_per_step": flops_step, "flop_factor": flop_factor,
-                   "recompute_segment_layers": seg, "activation_pool_gb": round(pool.numel() / 2 ** 30, 3),
+                   "recompute_segment_layers": seg, "stage": args.stage, "activation_pool_gb": round(pool.numel() / 2 ** 30, 3),
                    "resident_hbm_gb": round(peak_hbm_bytes / 2 ** 30, 2)},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
         "context": "paper: 163 TFLOP/s per A100 = 52% of peak, end-to-end on 3072 GPUs, recompute counted (x4)",

@@ -262,6 +262,46 @@ int ptdp_schedule_run_ckpt(ptdp_chunk* const* chunks, int v, int m, const ptdp_s
                            void* ckpt_pool, size_t slot_bytes, int n_slots, int seg_layers,
                            void* seg_stash, void* workspace, void* stream);
 
+/* ------------------------------------------- first / last stage extras */
+/* What the first and last pipeline stage run besides transformer layers: the
+ * V x h word table and s x h position table of eq. (2), and the logit layer of
+ * the appendix (2 b s h V FLOPs forward, 4 b s h V backward).  The paper fixes
+ * no more than that; the readings taken are: hidden dropout after the
+ * embedding sum (stream of layer id PTDP_EMBED_LAYER, site 0), a final
+ * LayerNorm before the logits, the word table shared by input and output, mean
+ * token loss.  One tensor-parallel shard holds the vocabulary rows
+ * [vocab_first, vocab_first + vocab_rows) (vocab_rows % 8 == 0): ids outside
+ * contribute zero rows / no target term, and maximum and sum of exponentials
+ * run over the shard's rows (the cross-shard reductions are the identity on
+ * one shard, as for the layers).  cfg supplies h, s, b, dtype, p_hidden,
+ * ln_eps, seed.  tokens / targets: dev int32 [s, b]. */
+#define PTDP_EMBED_LAYER 0x7fffffffu
+
+/* Bytes of scratch for the three calls below. */
+size_t ptdp_lm_workspace_bytes(const ptdp_layer_cfg* cfg, int vocab_rows);
+/* 2 b s h vocab_rows: the shard's logit GEMM, forward. */
+int64_t ptdp_logit_flops_fwd(const ptdp_layer_cfg* cfg, int vocab_rows);
+
+/* x[i,j,:] = Drop(e_word[tokens[i,j] - vocab_first] + e_pos[i]);  e_word
+ * [vocab_rows, h], e_pos [s, h], x [T, h] out, all dev in cfg's dtype. */
+int ptdp_embedding_forward(const ptdp_layer_cfg* cfg, int vocab_first, int vocab_rows, const int32_t* tokens,
+                           const void* e_word, const void* e_pos, void* x, int64_t microbatch, void* stream);
+/* d_e_word [vocab_rows, h] and d_e_pos [s, h] (dev fp32) += the gradients for
+ * dx [T, h].  Rows of repeated ids are added in token order (no atomics). */
+int ptdp_embedding_backward(const ptdp_layer_cfg* cfg, int vocab_first, int vocab_rows, const int32_t* tokens,
+                            const void* dx, float* d_e_word, float* d_e_pos, void* workspace,
+                            int64_t microbatch, void* stream);
+/* Forward and backward of the model head for one microbatch (the last stage
+ * runs them back to back under 1F1B): u = LN(y); logits = u e_word^T;
+ * token_loss[r] = log sum_v exp(logit[r,v]) - logit[r,target[r]] (dev fp32
+ * [T]); loss[0] = mean (dev fp32); then gradients of loss_scale * loss:
+ * dy [T, h] out (may alias y), d_lnf_g / d_lnf_b [h] and d_e_word
+ * [vocab_rows, h] (dev fp32) +=. */
+int ptdp_lm_head_step(const ptdp_layer_cfg* cfg, int vocab_first, int vocab_rows, const void* y, const void* lnf_g,
+                      const void* lnf_b, const void* e_word, const int32_t* targets, float loss_scale,
+                      float* loss, float* token_loss, void* dy, float* d_lnf_g, float* d_lnf_b,
+                      float* d_e_word, void* workspace, void* stream);
+
 /* ------------------------------------------------- single kernels (per-op) */
 /* Exported for per-operation parity tests and roofline measurements.  dtype as
  * in ptdp_layer_cfg; all pointers dev; rows = T. */
@@ -332,7 +372,7 @@ int ptdp_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse,
 enum {
   PTDP_K_GEMM_NN = 0, PTDP_K_GEMM_NT, PTDP_K_GEMM_TN, PTDP_K_ATTN_FWD, PTDP_K_ATTN_BWD,
   PTDP_K_LN_FWD, PTDP_K_LN_BWD, PTDP_K_GELU_FWD, PTDP_K_GELU_BWD, PTDP_K_BDA_FWD, PTDP_K_BDA_BWD,
-  PTDP_K_COLSUM, PTDP_K_OTHER, PTDP_K_NFAMILIES
+  PTDP_K_COLSUM, PTDP_K_OTHER, PTDP_K_EMBED, PTDP_K_XENT, PTDP_K_NFAMILIES
 };
 typedef struct ptdp_prof_entry {
   double ms;     /* summed elapsed time of the family's launches */

@@ -26,7 +26,7 @@ GELU_ERF, GELU_TANH = 0, 1
 GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 STASH_FIELDS = ("X", "U", "QKV", "CTX", "X1", "U2", "Z", "G", "MU1", "RSTD1", "MU2", "RSTD2", "LSE")
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
-PROF_FAMILIES = 13
+PROF_FAMILIES = 15
 
 
 class PtdpError(RuntimeError):
@@ -93,6 +93,11 @@ SIGNATURES = {
                                C.POINTER(_vp), C.POINTER(_vp), _vp, _sz, _i, _vp, _vp]),
     "ptdp_schedule_run_ckpt": (_i, [C.POINTER(_vp), _i, _i, C.POINTER(Step), _i, C.POINTER(_vp), C.POINTER(_vp),
                                     C.POINTER(_vp), C.POINTER(_vp), _vp, _sz, _i, _i, _vp, _vp, _vp]),
+    "ptdp_lm_workspace_bytes": (_sz, [_cfgp, _i]),
+    "ptdp_logit_flops_fwd": (_i64, [_cfgp, _i]),
+    "ptdp_embedding_forward": (_i, [_cfgp, _i, _i, _vp, _vp, _vp, _vp, _i64, _vp]),
+    "ptdp_embedding_backward": (_i, [_cfgp, _i, _i, _vp, _vp, _vp, _vp, _vp, _i64, _vp]),
+    "ptdp_lm_head_step": (_i, [_cfgp, _i, _i, _vp, _vp, _vp, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "ptdp_layernorm_fwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _f, _vp]),
     "ptdp_layernorm_bwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _vp]),
     "ptdp_bias_gelu_fwd": (_i, [_i, _i, _vp, _vp, _vp, _i, _i, _vp]),

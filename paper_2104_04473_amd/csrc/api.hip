@@ -602,6 +602,100 @@ int ptdp_schedule_run_ckpt(ptdp_chunk* const* chunks, int v, int m, const ptdp_s
                            slot_bytes, n_slots, seg_layers, seg_stash, workspace, stream);
 }
 
+// --------------------------------------------------------------------- first / last stage extras
+namespace {
+enum { LM_U = 0, LM_MU, LM_RSTD, LM_LOGITS, LM_DU, LM_COLSUM, LM_SPLITK, LM_N };
+struct LmLayout {
+  size_t off[LM_N];
+  size_t total;
+};
+LmLayout lm_layout(const ptdp_layer_cfg* c, int vrows) {
+  const Dims d = dims_of(c);
+  size_t sz[LM_N];
+  sz[LM_U] = sz[LM_DU] = d.T * d.h * d.esz;   // LM_DU doubles as the masked gradient of the embedding backward
+  sz[LM_MU] = sz[LM_RSTD] = d.T * sizeof(float);
+  sz[LM_LOGITS] = (size_t)d.T * vrows * d.esz;
+  sz[LM_COLSUM] = colsum_scratch_bytes((int)d.T, (int)(2 * d.h));
+  sz[LM_SPLITK] = c->dtype == PTDP_BF16 ? gemm_workspace_bytes() : 0;
+  LmLayout L;
+  size_t o = 0;
+  for (int i = 0; i < LM_N; ++i) {
+    L.off[i] = o;
+    o += align256(sz[i]);
+  }
+  L.total = o;
+  return L;
+}
+int lm_check(const ptdp_layer_cfg* cfg, int v0, int vrows) {
+  const int rc = validate(cfg);
+  if (rc != PTDP_OK) return rc;
+  if (v0 < 0 || vrows <= 0 || vrows % 8 != 0 || (int64_t)v0 + vrows > 0x7fffffffll) return PTDP_E_INVALID_ARG;
+  return PTDP_OK;
+}
+}  // namespace
+
+size_t ptdp_lm_workspace_bytes(const ptdp_layer_cfg* cfg, int vocab_rows) {
+  if (lm_check(cfg, 0, vocab_rows) != PTDP_OK) return 0;
+  return lm_layout(cfg, vocab_rows).total;
+}
+
+int64_t ptdp_logit_flops_fwd(const ptdp_layer_cfg* cfg, int vocab_rows) {
+  if (lm_check(cfg, 0, vocab_rows) != PTDP_OK) return -1;
+  return 2ll * cfg->b * cfg->s * cfg->h * vocab_rows;
+}
+
+int ptdp_embedding_forward(const ptdp_layer_cfg* cfg, int vocab_first, int vocab_rows, const int32_t* tokens,
+                           const void* e_word, const void* e_pos, void* x, int64_t microbatch, void* stream) {
+  PTDP_TRY(lm_check(cfg, vocab_first, vocab_rows));
+  if (!tokens || !e_word || !e_pos || !x) return PTDP_E_NULL_PTR;
+  if (microbatch < 0) return PTDP_E_INVALID_ARG;
+  return launch_embed_fwd(cfg->dtype, tokens, e_word, e_pos, x, cfg->s, cfg->b, cfg->h, vocab_first, vocab_rows,
+                          cfg->p_hidden, dropout_key(cfg->seed, PTDP_EMBED_LAYER, 0, (uint64_t)microbatch),
+                          (hipStream_t)stream);
+}
+
+int ptdp_embedding_backward(const ptdp_layer_cfg* cfg, int vocab_first, int vocab_rows, const int32_t* tokens,
+                            const void* dx, float* d_e_word, float* d_e_pos, void* workspace, int64_t microbatch,
+                            void* stream) {
+  PTDP_TRY(lm_check(cfg, vocab_first, vocab_rows));
+  if (!tokens || !dx || !d_e_word || !d_e_pos || !workspace) return PTDP_E_NULL_PTR;
+  if (microbatch < 0) return PTDP_E_INVALID_ARG;
+  const LmLayout L = lm_layout(cfg, vocab_rows);
+  return launch_embed_bwd(cfg->dtype, tokens, dx, (char*)workspace + L.off[LM_DU], d_e_word, d_e_pos, cfg->s, cfg->b,
+                          cfg->h, vocab_first, vocab_rows, cfg->p_hidden,
+                          dropout_key(cfg->seed, PTDP_EMBED_LAYER, 0, (uint64_t)microbatch), (hipStream_t)stream);
+}
+
+int ptdp_lm_head_step(const ptdp_layer_cfg* cfg, int vocab_first, int vocab_rows, const void* y, const void* lnf_g,
+                      const void* lnf_b, const void* e_word, const int32_t* targets, float loss_scale, float* loss,
+                      float* token_loss, void* dy, float* d_lnf_g, float* d_lnf_b, float* d_e_word, void* workspace,
+                      void* stream) {
+  PTDP_TRY(lm_check(cfg, vocab_first, vocab_rows));
+  if (!y || !lnf_g || !lnf_b || !e_word || !targets || !loss || !token_loss || !dy || !d_lnf_g || !d_lnf_b ||
+      !d_e_word || !workspace)
+    return PTDP_E_NULL_PTR;
+  if (!(loss_scale == loss_scale) || std::isinf(loss_scale)) return PTDP_E_INVALID_ARG;
+  const Dims d = dims_of(cfg);
+  if (d.h > 8 * 512 * (cfg->dtype == PTDP_BF16 ? 8 : 4)) return PTDP_E_UNSUPPORTED;
+  const LmLayout L = lm_layout(cfg, vocab_rows);
+  char* W = (char*)workspace;
+  auto wf = [&](int f) { return (void*)(W + L.off[f]); };
+  hipStream_t st = (hipStream_t)stream;
+  const int T = (int)d.T, h = (int)d.h, dt = cfg->dtype;
+  void* sk = wf(LM_SPLITK);
+  const size_t skb = L.total - L.off[LM_SPLITK];
+  PTDP_TRY(launch_layernorm_fwd(dt, y, lnf_g, lnf_b, wf(LM_U), (float*)wf(LM_MU), (float*)wf(LM_RSTD), nullptr, T, h,
+                                cfg->ln_eps, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(LM_U), e_word, wf(LM_LOGITS), nullptr, T, vocab_rows, h, 0, 0, sk, skb, st));
+  PTDP_TRY(launch_xent(dt, wf(LM_LOGITS), targets, token_loss, loss, T, vocab_rows, vocab_first, loss_scale / (float)T,
+                       st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NN, wf(LM_LOGITS), e_word, wf(LM_DU), nullptr, T, h, vocab_rows, 0, 0, sk, skb, st));
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, wf(LM_LOGITS), wf(LM_U), d_e_word, nullptr, vocab_rows, h, T, 1, 1, sk, skb, st));
+  PTDP_TRY(launch_layernorm_bwd(dt, wf(LM_DU), y, lnf_g, (const float*)wf(LM_MU), (const float*)wf(LM_RSTD), nullptr, dy,
+                                d_lnf_g, d_lnf_b, wf(LM_COLSUM), T, h, st));
+  return PTDP_OK;
+}
+
 // ------------------------------------------------------------------------- single-kernel exports
 static int check_dtype(int dtype) { return (dtype == PTDP_F32 || dtype == PTDP_BF16) ? PTDP_OK : PTDP_E_INVALID_ARG; }
 static int check_rw(int dtype, int rows, int width) {
@@ -746,7 +840,8 @@ int ptdp_prof_collect(ptdp_prof_entry* out) {
 const char* ptdp_prof_family_name(int family) {
   static const char* names[PTDP_K_NFAMILIES] = {"gemm_nn", "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd",
                                                 "layernorm_fwd", "layernorm_bwd", "bias_gelu_fwd", "bias_gelu_bwd",
-                                                "bias_dropout_add_fwd", "bias_dropout_add_bwd", "colsum", "other"};
+                                                "bias_dropout_add_fwd", "bias_dropout_add_bwd", "colsum", "other",
+                                                "embedding", "loss"};
   return (family >= 0 && family < PTDP_K_NFAMILIES) ? names[family] : "?";
 }
 

@@ -89,6 +89,15 @@ inline uint64_t dropout_key(uint64_t seed, uint32_t layer, uint32_t site, uint64
   return k;
 }
 inline uint32_t dropout_threshold(float p) { return (uint32_t)((double)p * 65536.0 + 0.5); }
+// keep flags of the N elements starting at flat index idx (idx % N == 0, N in {4, 8}).
+template <int N> __device__ __forceinline__ void keep_flags(uint64_t key, uint64_t idx, uint32_t thr, bool* keep) {
+#pragma unroll
+  for (int w = 0; w < N / 4; ++w) {
+    const uint64_t r = mix64(key + kGolden * ((idx >> 2) + w));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) keep[4 * w + j] = (uint32_t)((r >> (16 * j)) & 0xffffu) >= thr;
+  }
+}
 
 // ---- launch bookkeeping -------------------------------------------------------
 // Brackets a launch with an event pair when profiling is on; records launch errors.
@@ -129,5 +138,12 @@ int launch_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, in
 int launch_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse, const void* dctx,
                     void* dqkv, float* delta, int s, int b, int heads, int dh, hipStream_t st);
 bool attn_dh_supported(int dtype, int dh);
+// first / last stage extras (lm_stage.hip)
+int launch_embed_fwd(int dtype, const int32_t* tokens, const void* e_word, const void* e_pos, void* x, int s, int b,
+                     int h, int v0, int vrows, float p, uint64_t key, hipStream_t st);
+int launch_embed_bwd(int dtype, const int32_t* tokens, const void* dx, void* dmasked, float* d_e_word, float* d_e_pos,
+                     int s, int b, int h, int v0, int vrows, float p, uint64_t key, hipStream_t st);
+int launch_xent(int dtype, void* logits, const int32_t* targets, float* token_loss, float* loss, int rows, int vrows,
+                int v0, float grad_scale, hipStream_t st);
 
 }  // namespace ptdp

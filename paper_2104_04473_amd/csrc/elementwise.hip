@@ -264,16 +264,6 @@ __global__ void bias_gelu_bwd_kernel(const T* dg, const T* __restrict__ z, const
 // ------------------------------------------------------------------------------------------------
 // bias + dropout + add
 // ------------------------------------------------------------------------------------------------
-// keep flags of the N elements starting at flat index idx (idx % N == 0, N in {4, 8}).
-template <int N> __device__ __forceinline__ void keep_flags(uint64_t key, uint64_t idx, uint32_t thr, bool* keep) {
-#pragma unroll
-  for (int w = 0; w < N / 4; ++w) {
-    const uint64_t r = mix64(key + kGolden * ((idx >> 2) + w));
-#pragma unroll
-    for (int j = 0; j < 4; ++j) keep[4 * w + j] = (uint32_t)((r >> (16 * j)) & 0xffffu) >= thr;
-  }
-}
-
 template <typename T>
 __global__ void bda_fwd_kernel(const T* __restrict__ in, const T* __restrict__ bias, const T* __restrict__ resid,
                                T* __restrict__ out, size_t total_vec, int nvec_row, uint64_t key, uint32_t thr,
