@@ -57,6 +57,7 @@ class LayerConfig:
     ln_eps: float = 1e-5
     gelu_tanh: bool = False
     seed: int = 0
+    causal: bool = True     # False: general mask (section 4.2, the kernel "used in models such as BERT")
 
     @property
     def dh(self):
@@ -145,10 +146,26 @@ def causal_softmax_rows(scores):
     return e / e.sum(axis=1, keepdims=True)
 
 
-def attention_core(qkv, cfg):
+MASK_FILL = -10000.0   # value a hidden score is replaced with under the general mask (a stated reading)
+
+
+def masked_softmax_rows(scores, hidden):
+    """Row softmax under a general mask: hidden[q, k] True replaces the scaled score by MASK_FILL before
+    the softmax, so a row with some visible key gives hidden keys probability exp(-10000 - max) = 0 and a
+    row with no visible key attends uniformly.  Returns (probs, log-sum-exp)."""
+    sc = np.where(hidden, MASK_FILL, scores)
+    mx = sc.max(axis=1, keepdims=True)
+    e = np.exp(sc - mx)
+    z = e.sum(axis=1, keepdims=True)
+    return e / z, (mx + np.log(z))[:, 0]
+
+
+def attention_core(qkv, cfg, mask=None):
     """Per (sample, local head): ctx = softmax(mask(q k^T / sqrt(dh))) v.
     qkv: [s, b, 3*hp].  Returns ctx [s, b, hp], probs [b, heads, s, s] and the
-    log-sum-exp of the scaled, masked scores [b, heads, s]."""
+    log-sum-exp of the scaled, masked scores [b, heads, s].
+    cfg.causal: implicit causal mask.  Otherwise mask [b, s, s] (nonzero = key hidden from query;
+    None = nothing hidden) is applied as in masked_softmax_rows."""
     s, b, al, dh, hp = cfg.s, cfg.b, cfg.heads_local, cfg.dh, cfg.hp
     ctx = np.zeros((s, b, hp))
     probs = np.zeros((b, al, s, s))
@@ -159,16 +176,22 @@ def attention_core(qkv, cfg):
             k = qkv[:, j, hp + e * dh: hp + (e + 1) * dh]
             v = qkv[:, j, 2 * hp + e * dh: 2 * hp + (e + 1) * dh]
             sc = (q @ k.T) / math.sqrt(dh)
-            p = causal_softmax_rows(sc)
+            if cfg.causal:
+                p = causal_softmax_rows(sc)
+                scm = np.where(np.tril(np.ones((s, s), dtype=bool)), sc, -np.inf)
+                mx = scm.max(axis=1)
+                lse[j, e] = mx + np.log(np.exp(scm - mx[:, None]).sum(axis=1))
+            else:
+                hidden = np.zeros((s, s), dtype=bool) if mask is None else (np.asarray(mask[j]) != 0)
+                p, lse[j, e] = masked_softmax_rows(sc, hidden)
             probs[j, e] = p
-            scm = np.where(np.tril(np.ones((s, s), dtype=bool)), sc, -np.inf)
-            mx = scm.max(axis=1)
-            lse[j, e] = mx + np.log(np.exp(scm - mx[:, None]).sum(axis=1))
             ctx[:, j, e * dh:(e + 1) * dh] = p @ v
     return ctx, probs, lse
 
 
-def attention_core_backward(dctx, qkv, probs, cfg):
+def attention_core_backward(dctx, qkv, probs, cfg, mask=None):
+    """Under the general mask a hidden score is a constant, so no gradient reaches q and k through it
+    (its probability still weighs v: that matters only for rows with no visible key)."""
     s, b, al, dh, hp = cfg.s, cfg.b, cfg.heads_local, cfg.dh, cfg.hp
     dqkv = np.zeros_like(qkv)
     for j in range(b):
@@ -181,6 +204,8 @@ def attention_core_backward(dctx, qkv, probs, cfg):
             dv = p.T @ dc
             dp = dc @ v.T
             ds = p * (dp - (dp * p).sum(axis=1, keepdims=True))
+            if not cfg.causal and mask is not None:
+                ds = np.where(np.asarray(mask[j]) != 0, 0.0, ds)
             dq = (ds @ k) / math.sqrt(dh)
             dk = (ds.T @ q) / math.sqrt(dh)
             dqkv[:, j, e * dh:(e + 1) * dh] = dq
@@ -221,16 +246,17 @@ def _f64(P):
     return {k: np.asarray(v, dtype=np.float64) for k, v in P.items()}
 
 
-def layer_forward(x, P, cfg, layer=0, microbatch=0):
+def layer_forward(x, P, cfg, layer=0, microbatch=0, mask=None):
     """x [s, b, h] -> (y [s, b, h], cache).  ``layer`` is the global layer
     index and ``microbatch`` the microbatch id; both only select the dropout
-    stream."""
+    stream.  ``mask`` [b, s, s]: general attention mask, used when cfg.causal is False."""
     P = _f64(P)
     x = np.asarray(x, dtype=np.float64)
     c = {"x": x}
     c["u"], c["mu1"], c["rstd1"] = layernorm(x, P["ln1_g"], P["ln1_b"], cfg.ln_eps)
     c["qkv"] = c["u"] @ P["w_qkv"] + P["b_qkv"]
-    c["ctx"], c["probs"], c["lse"] = attention_core(c["qkv"], cfg)
+    c["mask"] = mask
+    c["ctx"], c["probs"], c["lse"] = attention_core(c["qkv"], cfg, mask)
     c["o"] = c["ctx"] @ P["w_o"]
     c["keep1"] = dropout_keep(cfg, layer, 0, microbatch)
     scale = dropout_hash.keep_scale(cfg.p_hidden)
@@ -272,7 +298,7 @@ def layer_backward(dy, P, cfg, cache):
     dx = dx1.copy()                                 # residual branch
     dctx = do @ P["w_o"].T
     G["w_o"] = flat(c["ctx"]).T @ flat(do)
-    dqkv = attention_core_backward(dctx, c["qkv"], c["probs"], cfg)
+    dqkv = attention_core_backward(dctx, c["qkv"], c["probs"], cfg, c.get("mask"))
     G["b_qkv"] = flat(dqkv).sum(axis=0)
     du = dqkv @ P["w_qkv"].T
     G["w_qkv"] = flat(c["u"]).T @ flat(dqkv)
