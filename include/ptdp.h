@@ -72,7 +72,7 @@ typedef struct ptdp_layer_cfg {
   uint32_t struct_size;
   int32_t h, a, t, s, b; /* full hidden, full heads, TP degree, sequence, microbatch */
   int32_t dtype;         /* PTDP_F32 or PTDP_BF16 */
-  int32_t causal;        /* must be 1: implicit causal mask (section 4.2) */
+  int32_t causal;        /* 1: implicit causal mask; 0: general mask, see ptdp_chunk_set_mask (section 4.2) */
   int32_t gelu_mode;     /* PTDP_GELU_ERF (default) or PTDP_GELU_TANH */
   float p_hidden;        /* dropout probability of the two bias+dropout+add sites, 0 <= p < 1 */
   float ln_eps;          /* LayerNorm epsilon (> 0) */
@@ -118,7 +118,7 @@ enum {
 /* ------------------------------------------------------------ host helpers */
 
 /* Checks a configuration: struct_size, h % a == 0, a % t == 0, (4h) % t == 0,
- * dh % 8 == 0, sizes > 0, 0 <= p_hidden < 1, ln_eps > 0, causal == 1, known
+ * dh % 8 == 0, sizes > 0, 0 <= p_hidden < 1, ln_eps > 0, causal in {0, 1}, known
  * dtype / gelu_mode.  bf16 needs dh in {32, 64, 96, 128, 160} for the MFMA attention
  * kernels, otherwise PTDP_E_UNSUPPORTED. */
 int ptdp_cfg_validate(const ptdp_layer_cfg* cfg);
@@ -171,6 +171,16 @@ int ptdp_chunk_n_layers(const ptdp_chunk* chunk);
  * chunk).  All twelve pointers must be non-NULL. */
 int ptdp_chunk_bind_params(ptdp_chunk* chunk, int layer, const ptdp_layer_params* dev_ptrs);
 int ptdp_chunk_bind_grads(ptdp_chunk* chunk, int layer, const ptdp_layer_grads* dev_ptrs);
+
+/* General attention mask for a chunk whose cfg.causal is 0 (section 4.2 names
+ * two fused softmax kernels: general masking, as in BERT-style models, and
+ * the implicit causal mask).  mask: dev bytes [b, s, s], 4-byte aligned,
+ * borrowed; mask[j][q][k] != 0 hides key k from query q of sample j; NULL
+ * (the default) hides nothing.  A hidden scaled score is replaced by -10000
+ * before the softmax: a query with some visible key gives hidden keys
+ * probability 0; a query with none attends uniformly; no gradient reaches q
+ * or k through a hidden score.  PTDP_E_INVALID_ARG on a causal chunk. */
+int ptdp_chunk_set_mask(ptdp_chunk* chunk, const uint8_t* mask);
 
 /* Forward of one layer for one microbatch (section 2.3):
  *   u = LN1(x); qkv = u Wqkv + bqkv; ctx = causal softmax(q k^T/sqrt(dh)) v per
@@ -358,6 +368,13 @@ size_t ptdp_gemm_workspace_bytes(void);
  * extended over both batched GEMMs): ctx [s, b, hp], lse [b, heads, s] fp32. */
 int ptdp_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, int b, int heads, int dh,
                   void* stream);
+/* The same with a general mask instead of the causal one (mask as in
+ * ptdp_chunk_set_mask; NULL = full bidirectional attention). */
+int ptdp_attn_masked_fwd(int dtype, const void* qkv, const uint8_t* mask, void* ctx, float* lse, int s, int b,
+                         int heads, int dh, void* stream);
+int ptdp_attn_masked_bwd(int dtype, const void* qkv, const uint8_t* mask, const void* ctx, const float* lse,
+                         const void* dctx, void* dqkv, float* delta, int s, int b, int heads, int dh,
+                         void* stream);
 /* dqkv [s, b, 3hp] from dctx; delta: dev scratch of b*heads*s floats. */
 int ptdp_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
                   float* delta, int s, int b, int heads, int dh, void* stream);

@@ -110,6 +110,9 @@ SIGNATURES = {
     "ptdp_gemm_workspace_bytes": (_sz, []),
     "ptdp_attn_fwd": (_i, [_i, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "ptdp_attn_bwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
+    "ptdp_attn_masked_fwd": (_i, [_i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
+    "ptdp_attn_masked_bwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
+    "ptdp_chunk_set_mask": (_i, [_vp, _vp]),
     "ptdp_prof_enable": (_i, [_i]),
     "ptdp_prof_collect": (_i, [C.POINTER(ProfEntry)]),
     "ptdp_prof_family_name": (C.c_char_p, [_i]),

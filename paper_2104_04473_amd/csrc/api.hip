@@ -67,7 +67,7 @@ static int validate(const ptdp_layer_cfg* c) {
   if (c->gelu_mode != PTDP_GELU_ERF && c->gelu_mode != PTDP_GELU_TANH) return PTDP_E_INVALID_ARG;
   if (!(c->p_hidden >= 0.f && c->p_hidden < 1.f)) return PTDP_E_INVALID_ARG;
   if (!(c->ln_eps > 0.f)) return PTDP_E_INVALID_ARG;
-  if (c->causal != 1) return c->causal == 0 ? PTDP_E_UNSUPPORTED : PTDP_E_INVALID_ARG;
+  if (c->causal != 0 && c->causal != 1) return PTDP_E_INVALID_ARG;
   const int dh = c->h / c->a;
   if (dh % 8 != 0 || c->h % 8 != 0) return PTDP_E_INVALID_ARG;
   if ((int64_t)c->s * c->b > (1ll << 30)) return PTDP_E_INVALID_ARG;
@@ -165,6 +165,7 @@ struct ptdp_chunk {
   std::vector<ptdp_layer_params> params;
   std::vector<ptdp_layer_grads> grads;
   std::vector<char> have_params, have_grads;
+  const uint8_t* mask = nullptr;   // general attention mask [b, s, s] (dev, borrowed); used when cfg.causal == 0
   StashLayout sl;
   WsLayout wl;
 };
@@ -255,6 +256,13 @@ int ptdp_chunk_bind_params(ptdp_chunk* chunk, int layer, const ptdp_layer_params
   return PTDP_OK;
 }
 
+int ptdp_chunk_set_mask(ptdp_chunk* chunk, const uint8_t* mask) {
+  if (!chunk) return PTDP_E_NULL_PTR;
+  if ((chunk->cfg.causal != 0 && mask) || ((uintptr_t)mask & 3)) return PTDP_E_INVALID_ARG;
+  chunk->mask = mask;
+  return PTDP_OK;
+}
+
 int ptdp_chunk_bind_grads(ptdp_chunk* chunk, int layer, const ptdp_layer_grads* g) {
   if (!chunk || !g) return PTDP_E_NULL_PTR;
   if (layer < 0 || layer >= chunk->n_layers) return PTDP_E_INVALID_ARG;
@@ -296,7 +304,7 @@ int ptdp_layer_forward(ptdp_chunk* ch, int layer, int64_t microbatch, const void
   PTDP_TRY(launch_gemm(c.dtype, PTDP_GEMM_NN, sf(PTDP_STASH_U), P.w_qkv, sf(PTDP_STASH_QKV), P.b_qkv, T, 3 * hp, h, 0,
                        0, sk, skb, st));
   PTDP_TRY(launch_attn_fwd(c.dtype, sf(PTDP_STASH_QKV), sf(PTDP_STASH_CTX), (float*)sf(PTDP_STASH_LSE), c.s, c.b,
-                           (int)d.al, (int)d.dh, st));
+                           (int)d.al, (int)d.dh, ch->mask, c.causal, st));
   PTDP_TRY(launch_gemm(c.dtype, PTDP_GEMM_NN, sf(PTDP_STASH_CTX), P.w_o, o, nullptr, T, h, hp, 0, 0, sk, skb, st));
   PTDP_TRY(launch_bda_fwd(c.dtype, o, P.b_o, x, sf(PTDP_STASH_X1), T, h, c.p_hidden,
                           dropout_key(c.seed, gl, 0, (uint64_t)microbatch), st));
@@ -348,7 +356,7 @@ int ptdp_layer_backward(ptdp_chunk* ch, int layer, int64_t microbatch, const voi
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_o, wf(WS_CTX), nullptr, T, hp, h, 0, 0, sk, skb, st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_CTX), wf(WS_H1), G.w_o, nullptr, hp, h, T, 1, 1, sk, skb, st));
   PTDP_TRY(launch_attn_bwd(dt, sf(PTDP_STASH_QKV), sf(PTDP_STASH_CTX), (const float*)sf(PTDP_STASH_LSE), wf(WS_CTX),
-                           wf(WS_QKV), (float*)wf(WS_DELTA), c.s, c.b, (int)d.al, (int)d.dh, st));
+                           wf(WS_QKV), (float*)wf(WS_DELTA), c.s, c.b, (int)d.al, (int)d.dh, ch->mask, c.causal, st));
   PTDP_TRY(launch_colsum(dt, wf(WS_QKV), G.b_qkv, cs, T, 3 * hp, st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_QKV), P.w_qkv, wf(WS_H2), nullptr, T, h, 3 * hp, 0, 0, sk, skb, st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_U), wf(WS_QKV), G.w_qkv, nullptr, h, 3 * hp, T, 1, 1, sk, skb, st));
@@ -791,7 +799,17 @@ int ptdp_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, int 
   if (s < 0 || b < 0 || heads < 0 || dh <= 0 || dh % 8 != 0) return PTDP_E_INVALID_ARG;
   if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
   if (!qkv || !ctx || !lse) return PTDP_E_NULL_PTR;
-  return launch_attn_fwd(dtype, qkv, ctx, lse, s, b, heads, dh, (hipStream_t)stream);
+  return launch_attn_fwd(dtype, qkv, ctx, lse, s, b, heads, dh, nullptr, 1, (hipStream_t)stream);
+}
+
+int ptdp_attn_masked_fwd(int dtype, const void* qkv, const uint8_t* mask, void* ctx, float* lse, int s, int b, int heads,
+                         int dh, void* stream) {
+  PTDP_TRY(check_dtype(dtype));
+  if (s < 0 || b < 0 || heads < 0 || dh <= 0 || dh % 8 != 0) return PTDP_E_INVALID_ARG;
+  if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
+  if (!qkv || !ctx || !lse) return PTDP_E_NULL_PTR;
+  if (mask && ((uintptr_t)mask & 3)) return PTDP_E_INVALID_ARG;
+  return launch_attn_fwd(dtype, qkv, ctx, lse, s, b, heads, dh, mask, 0, (hipStream_t)stream);
 }
 
 int ptdp_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
@@ -800,7 +818,17 @@ int ptdp_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse,
   if (s < 0 || b < 0 || heads < 0 || dh <= 0 || dh % 8 != 0) return PTDP_E_INVALID_ARG;
   if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
   if (!qkv || !ctx || !lse || !dctx || !dqkv || !delta) return PTDP_E_NULL_PTR;
-  return launch_attn_bwd(dtype, qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, (hipStream_t)stream);
+  return launch_attn_bwd(dtype, qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, nullptr, 1, (hipStream_t)stream);
+}
+
+int ptdp_attn_masked_bwd(int dtype, const void* qkv, const uint8_t* mask, const void* ctx, const float* lse,
+                         const void* dctx, void* dqkv, float* delta, int s, int b, int heads, int dh, void* stream) {
+  PTDP_TRY(check_dtype(dtype));
+  if (s < 0 || b < 0 || heads < 0 || dh <= 0 || dh % 8 != 0) return PTDP_E_INVALID_ARG;
+  if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
+  if (!qkv || !ctx || !lse || !dctx || !dqkv || !delta) return PTDP_E_NULL_PTR;
+  if (mask && ((uintptr_t)mask & 3)) return PTDP_E_INVALID_ARG;
+  return launch_attn_bwd(dtype, qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, mask, 0, (hipStream_t)stream);
 }
 
 // ----------------------------------------------------------------------------------- profiling

@@ -28,11 +28,15 @@ template <> __device__ __forceinline__ void st<bf16_t>(bf16_t* p, float v) { *p 
 // rowwise kernels: grid (s, heads, b), one wave per block; lane owns dims lane, lane+64, ... (dh <= 256)
 // ------------------------------------------------------------------------------------------------
 constexpr int kMaxDimsPerLane = 4;
+// General mask (section 4.2: the fused softmax "with general masking"): a hidden score is replaced
+// by this value before the softmax, so a row without any visible key attends uniformly, and no
+// gradient flows to q and k through a hidden score.  mask is [b, s, s] bytes, nonzero = hidden.
+constexpr float kMaskFill = -10000.f;
 
 template <typename T>
 __global__ void __launch_bounds__(64)
 attn_fwd_rowwise(const T* __restrict__ qkv, T* __restrict__ ctx, float* __restrict__ lse, int s, int b, int heads,
-                 int dh) {
+                 int dh, const uint8_t* __restrict__ mask, int causal) {
   const int i = blockIdx.x, e = blockIdx.y, j = blockIdx.z, lane = threadIdx.x;
   const int hp = heads * dh;
   const size_t rs = (size_t)b * 3 * hp;  // token stride
@@ -46,7 +50,9 @@ attn_fwd_rowwise(const T* __restrict__ qkv, T* __restrict__ ctx, float* __restri
     acc[c] = 0.f;
   }
   float m = -INFINITY, l = 0.f;
-  for (int kk = 0; kk <= i; ++kk) {
+  const int kend = causal ? i : s - 1;
+  const uint8_t* mrow = (!causal && mask) ? mask + ((size_t)j * s + i) * s : nullptr;
+  for (int kk = 0; kk <= kend; ++kk) {
     const T* kr = base + (size_t)kk * rs + hp;
     const T* vr = kr + hp;
     float dot = 0.f;
@@ -55,7 +61,8 @@ attn_fwd_rowwise(const T* __restrict__ qkv, T* __restrict__ ctx, float* __restri
       const int d = lane + 64 * c;
       if (d < dh) dot += q[c] * ld(kr + d);
     }
-    const float sc = wave_sum(dot) * scale;
+    float sc = wave_sum(dot) * scale;
+    if (mrow && mrow[kk]) sc = kMaskFill;
     const float mn = fmaxf(m, sc);
     const float corr = __expf(m - mn), p = __expf(sc - mn);
     l = l * corr + p;
@@ -91,7 +98,8 @@ attn_delta_rowwise(const T* __restrict__ ctx, const T* __restrict__ dctx, float*
 template <typename T>
 __global__ void __launch_bounds__(64)
 attn_bwd_dq_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, const float* __restrict__ lse,
-                    const float* __restrict__ delta, T* __restrict__ dqkv, int s, int b, int heads, int dh) {
+                    const float* __restrict__ delta, T* __restrict__ dqkv, int s, int b, int heads, int dh,
+                    const uint8_t* __restrict__ mask, int causal) {
   const int i = blockIdx.x, e = blockIdx.y, j = blockIdx.z, lane = threadIdx.x;
   const int hp = heads * dh;
   const size_t rs = (size_t)b * 3 * hp;
@@ -106,7 +114,9 @@ attn_bwd_dq_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, const
     dc[c] = d < dh ? ld(dctx + ((size_t)i * b + j) * hp + (size_t)e * dh + d) : 0.f;
     acc[c] = 0.f;
   }
-  for (int kk = 0; kk <= i; ++kk) {
+  const int kend = causal ? i : s - 1;
+  const uint8_t* mrow = (!causal && mask) ? mask + ((size_t)j * s + i) * s : nullptr;
+  for (int kk = 0; kk <= kend; ++kk) {
     const T* kr = base + (size_t)kk * rs + hp;
     const T* vr = kr + hp;
     float dot = 0.f, dpv = 0.f;
@@ -118,8 +128,9 @@ attn_bwd_dq_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, const
       dot += q[c] * kv[c];
       if (d < dh) dpv += dc[c] * ld(vr + d);
     }
-    const float p = __expf(wave_sum(dot) * scale - L);
-    const float ds = p * (wave_sum(dpv) - D) * scale;
+    const bool hidden = mrow && mrow[kk];
+    const float p = __expf((hidden ? kMaskFill : wave_sum(dot) * scale) - L);
+    const float ds = hidden ? 0.f : p * (wave_sum(dpv) - D) * scale;
 #pragma unroll
     for (int c = 0; c < kMaxDimsPerLane; ++c) acc[c] += ds * kv[c];
   }
@@ -134,7 +145,8 @@ attn_bwd_dq_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, const
 template <typename T>
 __global__ void __launch_bounds__(64)
 attn_bwd_dkv_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, const float* __restrict__ lse,
-                     const float* __restrict__ delta, T* __restrict__ dqkv, int s, int b, int heads, int dh) {
+                     const float* __restrict__ delta, T* __restrict__ dqkv, int s, int b, int heads, int dh,
+                     const uint8_t* __restrict__ mask, int causal) {
   const int kk = blockIdx.x, e = blockIdx.y, j = blockIdx.z, lane = threadIdx.x;
   const int hp = heads * dh;
   const size_t rs = (size_t)b * 3 * hp;
@@ -148,7 +160,7 @@ attn_bwd_dkv_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, cons
     vv[c] = d < dh ? ld(base + (size_t)kk * rs + 2 * hp + d) : 0.f;
     dk[c] = dv[c] = 0.f;
   }
-  for (int i = kk; i < s; ++i) {
+  for (int i = causal ? kk : 0; i < s; ++i) {
     const T* qr = base + (size_t)i * rs;
     const T* dr = dctx + ((size_t)i * b + j) * hp + (size_t)e * dh;
     float qv[kMaxDimsPerLane], dc[kMaxDimsPerLane];
@@ -162,8 +174,9 @@ attn_bwd_dkv_rowwise(const T* __restrict__ qkv, const T* __restrict__ dctx, cons
       dpv += dc[c] * vv[c];
     }
     const size_t st_i = ((size_t)j * heads + e) * s + i;
-    const float p = __expf(wave_sum(dot) * scale - lse[st_i]);
-    const float ds = p * (wave_sum(dpv) - delta[st_i]) * scale;
+    const bool hidden = !causal && mask && mask[((size_t)j * s + i) * s + kk];
+    const float p = __expf((hidden ? kMaskFill : wave_sum(dot) * scale) - lse[st_i]);
+    const float ds = hidden ? 0.f : p * (wave_sum(dpv) - delta[st_i]) * scale;
 #pragma unroll
     for (int c = 0; c < kMaxDimsPerLane; ++c) {
       dv[c] += p * dc[c];
@@ -312,6 +325,16 @@ __device__ __forceinline__ void store_cols(bf16_t* out_row, const f32x16_t (&acc
     }
 }
 
+// Hidden flags of keys key .. key+3 of one mask row as the four bytes of a word (keys >= s read as 0).
+__device__ __forceinline__ uint32_t mask_word(const uint8_t* __restrict__ mrow, int key, int s, bool aligned) {
+  if (aligned && key < s) return *reinterpret_cast<const uint32_t*>(mrow + key);   // s % 4 == 0: key + 3 < s
+  uint32_t w = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (key + i < s) w |= (uint32_t)mrow[key + i] << (8 * i);
+  return w;
+}
+
 // Work assignment.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: every block of one
 // (sample, head) pair goes to the same XCD so that the pair's K and V stay in that L2, and each XCD
 // takes its pairs one after the other.  Returns false for surplus ids.  `blk` counts up within a pair.
@@ -333,10 +356,10 @@ inline int attn_grid(int nblk, int heads, int b) { return 8 * ((heads * b + 7) /
 // vector ALU work, not by MFMA: the output is rescaled only when some row's running maximum moved,
 // the mask is applied only on tiles that touch the diagonal, and exponentials and bf16 conversions
 // are single instructions.
-template <int DH>
+template <int DH, bool CAUSAL>
 __global__ void __launch_bounds__(kAttnThreads, DH > 128 ? 1 : 2)
 attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* __restrict__ lse, int s, int b,
-              int heads) {
+              int heads, const uint8_t* __restrict__ mask) {
   constexpr int NKK = DH / 16, NDT = DH / 32;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* k_lds = smem;
@@ -364,7 +387,10 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
   float m_run = -INFINITY, l_run = 0.f;
 
   const int q_last_blk = min(s, (qblk + 1) * kBQ) - 1;
-  const int ntiles = q_last_blk / kBKV + 1;
+  const int ntiles = CAUSAL ? q_last_blk / kBKV + 1 : (s + kBKV - 1) / kBKV;
+  const uint8_t* mrow = (!CAUSAL && mask) ? mask + ((size_t)j * s + min(my_q, s - 1)) * s : nullptr;
+  const bool aligned = (s & 3) == 0;
+  const float fill = kMaskFill * sqrtf((float)DH);   // times 1/sqrt(dh) gives the fill value
   TileMap<DH> map;
   map.init(rs);
   TileRegs<DH> tr;
@@ -373,8 +399,15 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
   __syncthreads();
   for (int kt = 0; kt < ntiles; ++kt) {
     const int key0 = kt * kBKV;
-    const bool active = key0 <= q_first + 31;  // else every key of the tile is in this wave's future
+    const bool active = !CAUSAL || key0 <= q_first + 31;  // else every key of the tile is in this wave's future
     map.load(tr, base + 2 * hp, rs, key0, s);
+    uint32_t mw[2][4];
+    if (!CAUSAL && mrow) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) mw[sub][g] = mask_word(mrow, key0 + sub * 32 + 8 * g + 4 * half, s, aligned);
+    }
 
     bf16x8_t pf[2][2];
     if (active) {
@@ -387,15 +420,34 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
           sacc[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(k_lds, sub, kk, l31, half), qf[kk],
                                                               sacc[sub], 0, 0, 0);
       }
-      // causal mask (also hides keys >= s, which are > every valid query); only tiles on the diagonal need it
-      if (key0 + kBKV - 1 > q_first) {
+      if (CAUSAL) {
+        // causal mask (also hides keys >= s, which are > every valid query); only tiles on the diagonal need it
+        if (key0 + kBKV - 1 > q_first) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+          for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            sacc[sub][r] = key > my_q ? -INFINITY : sacc[sub][r];
-          }
+            for (int r = 0; r < 16; ++r) {
+              const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+              sacc[sub][r] = key > my_q ? -INFINITY : sacc[sub][r];
+            }
+        }
+      } else {
+        if (mrow) {
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              sacc[sub][r] = ((mw[sub][r >> 2] >> (8 * (r & 3))) & 0xffu) ? fill : sacc[sub][r];
+        }
+        if (key0 + kBKV > s) {   // keys past the end of the sequence do not exist
+#pragma unroll
+          for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+              sacc[sub][r] = key >= s ? -INFINITY : sacc[sub][r];
+            }
+        }
       }
       float mx = m_run;
 #pragma unroll
@@ -451,10 +503,11 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
 // needs atomics: one owns 64 queries and produces dQ, one owns 64 keys and produces dK and dV.
 //   dP = dO V^T, dS = P o (dP - delta), dQ = dS K / sqrt(dh), dK = dS^T Q / sqrt(dh), dV = P^T dO
 // ------------------------------------------------------------------------------------------------
-template <int DH>
+template <int DH, bool CAUSAL>
 __global__ void __launch_bounds__(kAttnThreads, DH >= 96 ? 1 : 2)
 attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
-                 const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads) {
+                 const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads,
+                 const uint8_t* __restrict__ mask) {
   constexpr int NKK = DH / 16, NDT = DH / 32;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* k_lds = smem;                          // K [key][dh]: S^T = K Q^T directly, dQ^T = K^T dS^T through tr reads
@@ -488,7 +541,10 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
   for (int d = 0; d < NDT; ++d) acc[d] = zero16();
 
   const int q_last_blk = min(s, (qblk + 1) * kBQ) - 1;
-  const int ntiles = q_last_blk / kBKV + 1;
+  const int ntiles = CAUSAL ? q_last_blk / kBKV + 1 : (s + kBKV - 1) / kBKV;
+  const uint8_t* mrow = (!CAUSAL && mask) ? mask + ((size_t)j * s + min(my_q, s - 1)) * s : nullptr;
+  const bool aligned = (s & 3) == 0;
+  const float fill = kMaskFill * sqrtf((float)DH);
   // the next K and V tiles travel in registers while this step's arithmetic runs
   TileMap<DH> map;
   map.init(rs);
@@ -505,18 +561,33 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
       map.load(kr, base + hp, rs, key0 + kBKV, s);
       map.load(vr, base + 2 * hp, rs, key0 + kBKV, s);
     }
-    if (key0 > q_first + 31) continue;
-    const bool diag = key0 + kBKV - 1 > q_first;   // only tiles on the diagonal need the mask
+    if (CAUSAL && key0 > q_first + 31) continue;
+    const bool diag = key0 + kBKV - 1 > q_first;   // only tiles on the diagonal need the causal mask
     bf16x8_t dsf[2][2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
+      uint32_t mw[4] = {0u, 0u, 0u, 0u};
+      if (!CAUSAL && mrow) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) mw[g] = mask_word(mrow, key0 + sub * 32 + 8 * g + 4 * half, s, aligned);
+      }
       f32x16_t sacc = zero16(), dp = zero16();
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(k_lds, sub, kk, l31, half), qf[kk], sacc, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_direct<DH>(v_lds, sub, kk, l31, half), dof[kk], dp, 0, 0, 0);
       }
-      if (diag) {
+      if (!CAUSAL) {
+        // a hidden score is the constant fill: its probability counts (through D) but it passes no gradient;
+        // keys past the end do not exist (an empty row's lse is so low that their exp2 would overflow)
+        const bool tail = key0 + kBKV > s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+          const bool hidden = ((mw[r >> 2] >> (8 * (r & 3))) & 0xffu) || (tail && key >= s);
+          sacc[r] = hidden ? 0.f : __builtin_amdgcn_exp2f(sacc[r] * c2 - L2) * (dp[r] - D);
+        }
+      } else if (diag) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = key0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
@@ -541,16 +612,22 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
   if (valid) store_cols<NDT>(dqkv + (size_t)my_q * rs + (size_t)j * 3 * hp + (size_t)e * DH, acc, scale, half);
 }
 
-template <int DH>
+constexpr int kMaskLdsStride = 68;   // bytes per key row of the staged mask tile ([key][query], padded)
+
+template <int DH, bool CAUSAL>
 __global__ void __launch_bounds__(kAttnThreads)
 attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
-                  const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads) {
+                  const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads,
+                  const uint8_t* __restrict__ mask) {
   constexpr int NKK = DH / 16, NDT = DH / 32;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* q_lds = smem;                           // Q  [query][dh]: S = Q K^T directly, dK^T = Q^T dS through tr reads
   char* do_lds = smem + TileGeom<DH>::BYTES;    // dO [query][dh]: dP = dO V^T directly, dV^T = dO^T P through tr reads
   float* lse_lds = reinterpret_cast<float*>(smem + 2 * TileGeom<DH>::BYTES);  // lse * log2(e), +inf past the end
   float* delta_lds = lse_lds + kBKV;
+  uint8_t* mask_lds = reinterpret_cast<uint8_t*>(delta_lds + kBKV);   // general mask only: [64 keys][68]
+  const bool use_mask = !CAUSAL && mask != nullptr;
+  const float fill = kMaskFill * sqrtf((float)DH);
 
   int kblk, e, j;  // the first key blocks see the most queries and start first
   if (!attn_map(blockIdx.x, (s + kBQ - 1) / kBQ, heads, b, &kblk, &e, &j)) return;
@@ -597,7 +674,7 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
       }
     }
   };
-  const int qt_first = (kblk * kBQ) / kBKV;
+  const int qt_first = CAUSAL ? (kblk * kBQ) / kBKV : 0;
   if constexpr (kPrefetch) {
     qmap.init(rs);
     domap.init(dors);
@@ -625,10 +702,17 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
         delta_lds[threadIdx.x] = q < s ? delta_h[q] : 0.f;
       }
     }
+    if (use_mask) {   // this tile of the mask, transposed to [key][query] so that a lane reads 4 queries at once
+      for (int idx = threadIdx.x; idx < kBKV * kBQ; idx += kAttnThreads) {
+        const int ql = idx / kBQ, kl = idx % kBQ;
+        const int q = q0 + ql, key = kblk * kBQ + kl;
+        mask_lds[kl * kMaskLdsStride + ql] = (q < s && key < s) ? mask[((size_t)j * s + q) * s + key] : (uint8_t)0;
+      }
+    }
     __syncthreads();
     if (qt + 1 < nq_tiles) fetch(q0 + kBKV);
-    if (q0 + kBKV - 1 < key_first) continue;  // every query of the tile precedes this wave's keys
-    const bool diag = q0 < key_first + 32;    // some query of the tile precedes some key of this wave
+    if (CAUSAL && q0 + kBKV - 1 < key_first) continue;  // every query of the tile precedes this wave's keys
+    const bool diag = CAUSAL && q0 < key_first + 32;    // some query of the tile precedes some key of this wave
     bf16x8_t pf[2][2], dsf[2][2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
@@ -644,13 +728,15 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
         const float4 L4 = *reinterpret_cast<const float4*>(lse_lds + ql);
         const float4 D4 = *reinterpret_cast<const float4*>(delta_lds + ql);
         const float Ls[4] = {L4.x, L4.y, L4.z, L4.w}, Ds[4] = {D4.x, D4.y, D4.z, D4.w};
+        const uint32_t mw = use_mask ? *reinterpret_cast<const uint32_t*>(mask_lds + (wave * 32 + l31) * kMaskLdsStride + ql) : 0u;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int r = 4 * g + i;
-          float p = __builtin_amdgcn_exp2f(sacc[r] * c2 - Ls[i]);   // lse = +inf past the end gives 0
+          const bool hidden = (mw >> (8 * i)) & 0xffu;
+          float p = __builtin_amdgcn_exp2f((hidden ? fill : sacc[r]) * c2 - Ls[i]);   // lse = +inf past the end gives 0
           if (diag) p = my_key > q0 + ql + i ? 0.f : p;
           sacc[r] = p;
-          dp[r] = p * (dp[r] - Ds[i]);
+          dp[r] = hidden ? 0.f : p * (dp[r] - Ds[i]);
         }
       }
       pf[sub][0] = pack_frag(sacc, 0);
@@ -714,38 +800,44 @@ bool attn_dh_supported(int dtype, int dh) {
 
 static inline double attn_flops(int s, int b, int heads, int dh) { return 4.0 * b * heads * (double)s * s * dh; }
 
-template <int DH>
-static int attn_fwd_mfma_t(const bf16_t* qkv, bf16_t* ctx, float* lse, int s, int b, int heads, hipStream_t stream) {
+template <int DH, bool CAUSAL>
+static int attn_fwd_mfma_t(const bf16_t* qkv, bf16_t* ctx, float* lse, int s, int b, int heads, const uint8_t* mask,
+                           hipStream_t stream) {
   constexpr int smem = 2 * TileGeom<DH>::BYTES;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_mfma<DH>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            smem) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_mfma<DH, CAUSAL>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return PTDP_E_HIP;
     attr_set = true;
   }
   const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
-  hipLaunchKernelGGL((attn_fwd_mfma<DH>), grid, dim3(kAttnThreads), smem, stream, qkv, ctx, lse, s, b, heads);
+  hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL>), grid, dim3(kAttnThreads), smem, stream, qkv, ctx, lse, s, b, heads, mask);
   return PTDP_OK;
 }
 
+// Without the causal mask every row is a full row: count the whole s x s square as executed too.
 int launch_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, int b, int heads, int dh,
-                    hipStream_t stream) {
+                    const uint8_t* mask, int causal, hipStream_t stream) {
   if (s == 0 || b == 0 || heads == 0) return PTDP_OK;
   if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
   Launch L(PTDP_K_ATTN_FWD, attn_flops(s, b, heads, dh), stream);
   int rc = PTDP_OK;
   if (dtype == PTDP_F32) {
     hipLaunchKernelGGL((attn_fwd_rowwise<float>), dim3(s, heads, b), dim3(64), 0, stream, (const float*)qkv,
-                       (float*)ctx, lse, s, b, heads, dh);
+                       (float*)ctx, lse, s, b, heads, dh, mask, causal);
   } else {
     const bf16_t* q = (const bf16_t*)qkv;
     bf16_t* c = (bf16_t*)ctx;
-    if (dh == 32) rc = attn_fwd_mfma_t<32>(q, c, lse, s, b, heads, stream);
-    else if (dh == 96) rc = attn_fwd_mfma_t<96>(q, c, lse, s, b, heads, stream);
-    else if (dh == 64) rc = attn_fwd_mfma_t<64>(q, c, lse, s, b, heads, stream);
-    else if (dh == 128) rc = attn_fwd_mfma_t<128>(q, c, lse, s, b, heads, stream);
-    else rc = attn_fwd_mfma_t<160>(q, c, lse, s, b, heads, stream);
+#define PTDP_ATTN_FWD(D) \
+  rc = causal ? attn_fwd_mfma_t<D, true>(q, c, lse, s, b, heads, mask, stream) \
+              : attn_fwd_mfma_t<D, false>(q, c, lse, s, b, heads, mask, stream)
+    if (dh == 32) PTDP_ATTN_FWD(32);
+    else if (dh == 96) PTDP_ATTN_FWD(96);
+    else if (dh == 64) PTDP_ATTN_FWD(64);
+    else if (dh == 128) PTDP_ATTN_FWD(128);
+    else PTDP_ATTN_FWD(160);
+#undef PTDP_ATTN_FWD
   }
   if (rc != PTDP_OK) return rc;
   return L.status();
@@ -753,58 +845,65 @@ int launch_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, in
 
 template <typename T>
 static int attn_bwd_rowwise_t(const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
-                              float* delta, int s, int b, int heads, int dh, hipStream_t stream) {
+                              float* delta, int s, int b, int heads, int dh, const uint8_t* mask, int causal,
+                              hipStream_t stream) {
   const dim3 grid(s, heads, b);
   hipLaunchKernelGGL((attn_delta_rowwise<T>), grid, dim3(64), 0, stream, (const T*)ctx, (const T*)dctx, delta, s, b,
                      heads, dh);
   hipLaunchKernelGGL((attn_bwd_dq_rowwise<T>), grid, dim3(64), 0, stream, (const T*)qkv, (const T*)dctx, lse, delta,
-                     (T*)dqkv, s, b, heads, dh);
+                     (T*)dqkv, s, b, heads, dh, mask, causal);
   hipLaunchKernelGGL((attn_bwd_dkv_rowwise<T>), grid, dim3(64), 0, stream, (const T*)qkv, (const T*)dctx, lse, delta,
-                     (T*)dqkv, s, b, heads, dh);
+                     (T*)dqkv, s, b, heads, dh, mask, causal);
   return PTDP_OK;
 }
 
-template <int DH>
+template <int DH, bool CAUSAL>
 static int attn_bwd_mfma_t(const bf16_t* qkv, const bf16_t* ctx, const float* lse, const bf16_t* dctx, bf16_t* dqkv,
-                           float* delta, int s, int b, int heads, hipStream_t stream) {
+                           float* delta, int s, int b, int heads, const uint8_t* mask, hipStream_t stream) {
   constexpr int smem_dq = 2 * TileGeom<DH>::BYTES;
-  constexpr int smem_dkv = 2 * TileGeom<DH>::BYTES + 2 * kBKV * (int)sizeof(float);
+  constexpr int smem_dkv = 2 * TileGeom<DH>::BYTES + 2 * kBKV * (int)sizeof(float) + (CAUSAL ? 0 : kBQ * kMaskLdsStride);
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq_mfma<DH>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq_mfma<DH, CAUSAL>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem_dq) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH>),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH, CAUSAL>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem_dkv) != hipSuccess)
       return PTDP_E_HIP;
     attr_set = true;
   }
-  const size_t rows = (size_t)s * b * heads;
-  hipLaunchKernelGGL(attn_delta_bf16, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, ctx, dctx, delta, s, b,
+  const size_t nrows = (size_t)s * b * heads;
+  hipLaunchKernelGGL(attn_delta_bf16, dim3((unsigned)((nrows + 3) / 4)), dim3(256), 0, stream, ctx, dctx, delta, s, b,
                      heads, DH);
   const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
-  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH>), grid, dim3(kAttnThreads), smem_dkv, stream, qkv, dctx, lse, delta, dqkv, s, b, heads);
-  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH>), grid, dim3(kAttnThreads), smem_dq, stream, qkv, dctx, lse, delta, dqkv, s, b, heads);
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH, CAUSAL>), grid, dim3(kAttnThreads), smem_dkv, stream, qkv, dctx, lse, delta, dqkv,
+                     s, b, heads, mask);
+  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH, CAUSAL>), grid, dim3(kAttnThreads), smem_dq, stream, qkv, dctx, lse, delta, dqkv, s,
+                     b, heads, mask);
   return PTDP_OK;
 }
 
 int launch_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,
-                    float* delta, int s, int b, int heads, int dh, hipStream_t stream) {
+                    float* delta, int s, int b, int heads, int dh, const uint8_t* mask, int causal, hipStream_t stream) {
   if (s == 0 || b == 0 || heads == 0) return PTDP_OK;
   if (!attn_dh_supported(dtype, dh)) return PTDP_E_UNSUPPORTED;
   Launch L(PTDP_K_ATTN_BWD, 2.0 * attn_flops(s, b, heads, dh), stream);
   int rc = PTDP_OK;
   if (dtype == PTDP_F32) {
-    rc = attn_bwd_rowwise_t<float>(qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, stream);
+    rc = attn_bwd_rowwise_t<float>(qkv, ctx, lse, dctx, dqkv, delta, s, b, heads, dh, mask, causal, stream);
   } else {
     const bf16_t* q = (const bf16_t*)qkv;
     const bf16_t* c = (const bf16_t*)ctx;
     const bf16_t* d = (const bf16_t*)dctx;
     bf16_t* o = (bf16_t*)dqkv;
-    if (dh == 32) rc = attn_bwd_mfma_t<32>(q, c, lse, d, o, delta, s, b, heads, stream);
-    else if (dh == 96) rc = attn_bwd_mfma_t<96>(q, c, lse, d, o, delta, s, b, heads, stream);
-    else if (dh == 64) rc = attn_bwd_mfma_t<64>(q, c, lse, d, o, delta, s, b, heads, stream);
-    else if (dh == 128) rc = attn_bwd_mfma_t<128>(q, c, lse, d, o, delta, s, b, heads, stream);
-    else rc = attn_bwd_mfma_t<160>(q, c, lse, d, o, delta, s, b, heads, stream);
+#define PTDP_ATTN_BWD(D) \
+  rc = causal ? attn_bwd_mfma_t<D, true>(q, c, lse, d, o, delta, s, b, heads, mask, stream) \
+              : attn_bwd_mfma_t<D, false>(q, c, lse, d, o, delta, s, b, heads, mask, stream)
+    if (dh == 32) PTDP_ATTN_BWD(32);
+    else if (dh == 96) PTDP_ATTN_BWD(96);
+    else if (dh == 64) PTDP_ATTN_BWD(64);
+    else if (dh == 128) PTDP_ATTN_BWD(128);
+    else PTDP_ATTN_BWD(160);
+#undef PTDP_ATTN_BWD
   }
   if (rc != PTDP_OK) return rc;
   return L.status();

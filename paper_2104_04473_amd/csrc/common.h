@@ -133,10 +133,12 @@ int launch_colsum(int dtype, const void* in, float* out, void* scratch, int rows
 size_t gemm_workspace_bytes();
 int launch_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N,
                 int K, int out_f32, int accumulate, void* ws, size_t ws_bytes, hipStream_t st);
+// mask: [b, s, s] bytes (nonzero = hidden) or null, used when causal == 0
 int launch_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, int b, int heads, int dh,
-                    hipStream_t st);
+                    const uint8_t* mask, int causal, hipStream_t st);
 int launch_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse, const void* dctx,
-                    void* dqkv, float* delta, int s, int b, int heads, int dh, hipStream_t st);
+                    void* dqkv, float* delta, int s, int b, int heads, int dh, const uint8_t* mask, int causal,
+                    hipStream_t st);
 bool attn_dh_supported(int dtype, int dh);
 // first / last stage extras (lm_stage.hip)
 int launch_embed_fwd(int dtype, const int32_t* tokens, const void* e_word, const void* e_pos, void* x, int s, int b,

@@ -50,7 +50,8 @@ def test_cfg_validation():
     assert ok(cfg(ln_eps=0.0)) == B.E_INVALID_ARG
     assert ok(cfg(s=0)) == B.E_INVALID_ARG
     assert ok(cfg(dtype=7)) == B.E_INVALID_ARG
-    assert ok(cfg(causal=0)) == B.E_UNSUPPORTED
+    assert ok(cfg(causal=0)) == B.OK            # general mask
+    assert ok(cfg(causal=2)) == B.E_INVALID_ARG
     assert ok(cfg(h=96, a=4, dtype=B.BF16)) == B.E_UNSUPPORTED      # dh = 24: no MFMA attention
     assert ok(cfg(h=100, a=5)) == B.E_INVALID_ARG                   # dh = 20 not a multiple of 8
     bad = cfg(); bad.struct_size = 12
