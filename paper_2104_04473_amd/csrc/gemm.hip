@@ -497,7 +497,14 @@ static int launch_bf16_mode(const void* A, const void* B, void* C, const void* b
   const int rem = (int)(tiles % ncu);
   const bool sk_out_ok = (out_f32 && accumulate && !bias) || !out_f32;
   int dp_cols = tiles_n;
-  if (ws != nullptr && ws_bytes >= gemm_workspace_bytes() && sk_out_ok && nk >= 64 && rem != 0 && rem * 100 < ncu * 88)
+  // Splitting the last round along k saves the idle share of that round and costs two more launches plus
+  // a round trip of the partial tiles through memory.  Fitted to measurements: about 1.8 us per k-step,
+  // 15 us fixed + 0.23 us per remainder tile; with C accumulated in fp32 the extra pass over C makes it pay
+  // only for long k.
+  const double sk_saved_us = (1.0 - (double)rem / ncu) * nk * 1.8;
+  const double sk_cost_us = 15.0 + rem * (out_f32 ? 0.6 : 0.23);
+  if (ws != nullptr && ws_bytes >= gemm_workspace_bytes() && sk_out_ok && rem != 0 && sk_saved_us > sk_cost_us &&
+      (!out_f32 || nk >= 64))
     dp_cols = (int)((tiles / ncu) * ncu / tiles_m);   // the rest is fewer than ncu tiles
   const int n_dp = dp_cols < tiles_n ? dp_cols * kBN : N;
   if (n_dp > 0) {
