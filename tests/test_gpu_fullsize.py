@@ -148,3 +148,112 @@ def test_interleaved_share_at_gpt3_shape_accounting():
     peak = B.ptdp_schedule_peak_inflight(4, 2, 8, 0)
     assert peak == 11
     assert abs(peak * 4 * per_layer / 2 ** 30 - 11 * 4 * payload / 2 ** 30) < 0.01
+
+
+def test_recompute_at_full_size_is_bit_identical():
+    """c4's chunk (4 layers of the 1T shape) with a checkpoint every 2 layers: outputs, input gradient and
+    sampled parameter gradients equal the stash-everything path bit for bit."""
+    w = SHAPES["c4"]
+    cfg = B.make_cfg(dtype=B.BF16, p_hidden=0.1, seed=0, **w)
+    n, seg = 4, 2
+    ch = B.Chunk(cfg, n, 0)
+    grads = []
+    for l in range(n):
+        P = synth.layer_params(w["h"], w["a"], w["t"], B.BF16, seed=1000 + l, device="cuda", zero_bias=True, ln_jitter=0.0)
+        G = synth.zero_grads(w["h"], w["a"], w["t"], "cuda")
+        ch.bind(l, P, G)
+        grads.append(G)
+    shape = (w["s"], w["b"], w["h"])
+    x = synth.activations(*shape, B.BF16, 10, "cuda"); dy = synth.activations(*shape, B.BF16, 11, "cuda")
+    ws = torch.empty(ch.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    stash = torch.empty(ch.stash_bytes(), dtype=torch.uint8, device="cuda")
+    y0 = torch.empty_like(x); dx0 = torch.empty_like(x)
+    B.check(ch.forward(0, x.data_ptr(), y0.data_ptr(), stash.data_ptr(), ws.data_ptr()), "fwd")
+    B.check(ch.backward(0, dy.data_ptr(), dx0.data_ptr(), stash.data_ptr(), ws.data_ptr()), "bwd")
+    sync()
+    keep = {(l, k): grads[l][k][:64].clone() for l in range(n) for k in ("w_qkv", "w_2", "ln1_g", "b_1")}
+    for G in grads:
+        for g in G.values():
+            g.zero_()
+    del stash
+    ckpt = torch.empty(ch.checkpoint_bytes(seg), dtype=torch.uint8, device="cuda")
+    seg_stash = torch.empty(seg * B.ptdp_layer_stash_bytes(C.byref(cfg)), dtype=torch.uint8, device="cuda")
+    y1 = torch.empty_like(x); dx1 = torch.empty_like(x)
+    B.check(ch.forward_ckpt(0, x.data_ptr(), y1.data_ptr(), ckpt.data_ptr(), seg, seg_stash.data_ptr(), ws.data_ptr()), "fwd")
+    B.check(ch.backward_ckpt(0, dy.data_ptr(), dx1.data_ptr(), ckpt.data_ptr(), seg, seg_stash.data_ptr(), ws.data_ptr()), "bwd")
+    sync()
+    assert torch.equal(y0, y1) and torch.equal(dx0, dx1)
+    for (l, k), v in keep.items():
+        assert torch.equal(v, grads[l][k][:64]), (l, k)
+    ch.close()
+
+
+def test_head_step_sampled_parity_at_full_size():
+    """Last-stage head at c4's shape (h = 25600, V/t = 6400): token losses and rows of dy for sampled tokens are
+    recomputed by the oracle's definition (each needs only that token's row of logits)."""
+    w = SHAPES["c4"]
+    cfg = B.make_cfg(dtype=B.BF16, p_hidden=0.1, seed=0, **w)
+    T, h, rows, v0 = w["s"] * w["b"], w["h"], 6400, 12800
+    y = synth.activations(w["s"], w["b"], h, B.BF16, 21, "cuda")
+    e_word = (0.02 * torch.randn((rows, h), generator=torch.Generator().manual_seed(5))).to(torch.bfloat16).cuda()
+    g = torch.ones(h, dtype=torch.bfloat16, device="cuda"); bb = torch.zeros_like(g)
+    rng = np.random.default_rng(3)
+    tgt = rng.integers(0, 51200, size=(w["s"], w["b"])).astype(np.int32)
+    tgt[:64, 0] = rng.integers(v0, v0 + rows, size=64)            # some targets inside this shard
+    tgt_d = torch.from_numpy(tgt).cuda()
+    loss = torch.zeros(1, device="cuda"); tl = torch.zeros(T, device="cuda")
+    dy = torch.empty_like(y)
+    dg = torch.zeros(h, device="cuda"); db = torch.zeros(h, device="cuda")
+    dw = torch.zeros((rows, h), device="cuda")
+    ws = torch.empty(B.ptdp_lm_workspace_bytes(C.byref(cfg), rows), dtype=torch.uint8, device="cuda")
+    B.check(B.ptdp_lm_head_step(C.byref(cfg), v0, rows, y.data_ptr(), g.data_ptr(), bb.data_ptr(), e_word.data_ptr(),
+                                tgt_d.data_ptr(), 1.0, loss.data_ptr(), tl.data_ptr(), dy.data_ptr(), dg.data_ptr(),
+                                db.data_ptr(), dw.data_ptr(), ws.data_ptr(), stream()), "head")
+    sync()
+    E = np64(e_word)
+    sample = [0, 1, 63, 64, 777, T - 1]
+    yv = np64(y).reshape(T, h)
+    got_dy = np64(dy).reshape(T, h)
+    want_rows = []
+    for t in sample:
+        u, mu, rstd = L.layernorm(yv[t:t + 1], np.ones(h), np.zeros(h), float(np.float32(cfg.ln_eps)))
+        logits = (u @ E.T)[0]
+        m = logits.max(); z = np.exp(logits - m).sum()
+        local = int(tgt.reshape(-1)[t]) - v0
+        inside = 0 <= local < rows
+        want = math.log(z) + m - (logits[local] if inside else 0.0)
+        assert abs(tl[t].item() - want) <= 2e-2 * abs(want), (t, tl[t].item(), want)
+        p = np.exp(logits - m) / z
+        if inside:
+            p[local] -= 1.0
+        du = (p / T) @ E
+        wdy, _, _ = L.layernorm_backward(du[None, :], yv[t:t + 1], np.ones(h), mu, rstd)
+        want_rows.append(wdy[0])
+        assert_close(got_dy[t], wdy[0], B.BF16, "dy row %d" % t, 2.0)   # a single row is noisier than the tensor
+    assert_close(got_dy[sample], np.array(want_rows), B.BF16, "sampled dy rows")
+    assert abs(loss.item() - np64(tl).mean()) <= 1e-5 * abs(loss.item())
+    assert np.isfinite(np64(dw)).all() and np.abs(np64(dw)).max() > 0
+
+
+def test_masked_attention_sampled_parity_at_full_sequence():
+    """General mask at s = 2048, dh = 128: sampled query rows of two heads against the oracle's definition."""
+    s, b, heads, dh = 2048, 1, 4, 128
+    hp = heads * dh
+    qkv = synth.activations(s, b, 3 * hp, B.BF16, 4, "cuda")
+    rng = np.random.default_rng(8)
+    mask = (rng.random((b, s, s)) < 0.4).astype(np.uint8)
+    mask[0, 100, :] = 1                                            # a row with no visible key
+    mask_d = torch.from_numpy(mask).cuda()
+    ctx = torch.empty((s, b, hp), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((b, heads, s), device="cuda")
+    B.check(B.ptdp_attn_masked_fwd(B.BF16, qkv.data_ptr(), mask_d.data_ptr(), ctx.data_ptr(), lse.data_ptr(), s, b,
+                                   heads, dh, stream()), "masked fwd")
+    sync()
+    q = np64(qkv)
+    for e in (0, heads - 1):
+        k = q[:, 0, hp + e * dh: hp + (e + 1) * dh]; v = q[:, 0, 2 * hp + e * dh: 2 * hp + (e + 1) * dh]
+        for i in (0, 100, 1023, 2047):
+            sc = (k @ q[i, 0, e * dh:(e + 1) * dh]) / math.sqrt(dh)
+            p, l = L.masked_softmax_rows(sc[None, :], mask[0, i][None, :] != 0)
+            assert_close(np64(ctx[i, 0, e * dh:(e + 1) * dh]), p[0] @ v, B.BF16, "ctx row %d head %d" % (i, e))
+            assert abs(lse[0, e, i].item() - l[0]) <= 3e-2
