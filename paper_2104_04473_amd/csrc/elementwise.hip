@@ -166,37 +166,59 @@ __global__ void layernorm_bwd_param_kernel(const T* __restrict__ du, const T* __
 }
 
 // out[c] += sum over parts of part[p][c]  (second stage of every column sum; fixed order).
-__global__ void colsum_finish_kernel(const float* __restrict__ part, int nparts, int stride, float* out0,
-                                     float* out1, int width) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= width) return;
-  // four independent partial sums keep several loads in flight; the order of additions is fixed
+// A workgroup owns 64 columns; its four waves each add a quarter of the parts (four independent partial
+// sums per lane keep loads in flight), and wave 0 adds the four quarter sums in order.
+__global__ void __launch_bounds__(256)
+colsum_finish_kernel(const float* __restrict__ part, int nparts, int stride, float* out0, float* out1, int width) {
+  __shared__ float red[2][4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  const int per = (nparts + 3) / 4, p0 = q * per, p1 = min(nparts, p0 + per);
   float a[4] = {0.f, 0.f, 0.f, 0.f}, b[4] = {0.f, 0.f, 0.f, 0.f};
-  int p = 0;
-  for (; p + 4 <= nparts; p += 4) {
+  if (c < width) {
+    int p = p0;
+    for (; p + 4 <= p1; p += 4) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      a[u] += part[(size_t)(p + u) * stride + c];
-      if (out1) b[u] += part[(size_t)(p + u) * stride + width + c];
+      for (int u = 0; u < 4; ++u) {
+        a[u] += part[(size_t)(p + u) * stride + c];
+        if (out1) b[u] += part[(size_t)(p + u) * stride + width + c];
+      }
+    }
+    for (; p < p1; ++p) {
+      a[0] += part[(size_t)p * stride + c];
+      if (out1) b[0] += part[(size_t)p * stride + width + c];
     }
   }
-  for (; p < nparts; ++p) {
-    a[0] += part[(size_t)p * stride + c];
-    if (out1) b[0] += part[(size_t)p * stride + width + c];
+  red[0][q][lane] = (a[0] + a[1]) + (a[2] + a[3]);
+  red[1][q][lane] = (b[0] + b[1]) + (b[2] + b[3]);
+  __syncthreads();
+  if (q == 0 && c < width) {
+    out0[c] += (red[0][0][lane] + red[0][1][lane]) + (red[0][2][lane] + red[0][3][lane]);
+    if (out1) out1[c] += (red[1][0][lane] + red[1][1][lane]) + (red[1][2][lane] + red[1][3][lane]);
   }
-  out0[c] += (a[0] + a[1]) + (a[2] + a[3]);
-  if (out1) out1[c] += (b[0] + b[1]) + (b[2] + b[3]);
 }
 
 // ------------------------------------------------------------------------------------------------
 // bias + GeLU
 // ------------------------------------------------------------------------------------------------
+// Standard normal CDF Phi(z) and density phi(z) from one exponential: with x = |z| / sqrt(2),
+// erfc(x) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-x^2), t = 1 / (1 + p x) (Abramowitz & Stegun 7.1.26,
+// absolute error below 1.5e-7), taken on the side that needs no cancellation.
+__device__ __forceinline__ float normal_cdf_pdf(float z, float* pdf) {
+  const float e = __expf(-0.5f * z * z);
+  const float t = __frcp_rn(1.f + 0.3275911f * 0.7071067811865476f * fabsf(z));
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float tail = 0.5f * poly * e;   // 0.5 erfc(|z| / sqrt(2))
+  *pdf = e * 0.3989422804014327f;
+  return z < 0.f ? tail : 1.f - tail;
+}
 template <int MODE> __device__ __forceinline__ float gelu_f(float z) {
   if (MODE == PTDP_GELU_TANH) {
     const float c = 0.7978845608028654f;
     return 0.5f * z * (1.f + tanhf(c * (z + 0.044715f * z * z * z)));
   }
-  return 0.5f * z * (1.f + erff(z * 0.7071067811865476f));
+  float pdf;
+  return z * normal_cdf_pdf(z, &pdf);
 }
 template <int MODE> __device__ __forceinline__ float gelu_grad_f(float z) {
   if (MODE == PTDP_GELU_TANH) {
@@ -204,9 +226,10 @@ template <int MODE> __device__ __forceinline__ float gelu_grad_f(float z) {
     const float th = tanhf(c * (z + 0.044715f * z * z * z));
     return 0.5f * (1.f + th) + 0.5f * z * (1.f - th * th) * c * (1.f + 3.f * 0.044715f * z * z);
   }
-  return 0.5f * (1.f + erff(z * 0.7071067811865476f)) + z * __expf(-0.5f * z * z) * 0.3989422804014327f;
+  float pdf;
+  const float cdf = normal_cdf_pdf(z, &pdf);
+  return cdf + z * pdf;
 }
-
 template <typename T, int MODE>
 __global__ void bias_gelu_fwd_kernel(const T* __restrict__ z, const T* __restrict__ bias, T* __restrict__ g,
                                      size_t total_vec, int nvec_row) {
@@ -402,7 +425,7 @@ int launch_layernorm_fwd(int dtype, const void* x, const void* gain, const void*
 static int colsum_finish(const float* part, int nparts, int stride, float* out0, float* out1, int width,
                          hipStream_t st) {
   Launch L(PTDP_K_COLSUM, (double)nparts * stride * sizeof(float), st);
-  hipLaunchKernelGGL(colsum_finish_kernel, dim3((width + 255) / 256), dim3(256), 0, st, part, nparts, stride, out0,
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3((width + 63) / 64), dim3(256), 0, st, part, nparts, stride, out0,
                      out1, width);
   return L.status();
 }
