@@ -224,6 +224,26 @@ def main():
                 "all_gemm_achieved": round(all_work / (all_ms * 1e-3) / 1e12, 2),
                 "all_gemm_share_of_step": round(all_ms / prof_steps / ms_per_step, 4)}
 
+    # ---- measured ceilings: register-resident MFMA loop, 1 GiB copy (events on the launch stream) ---------------
+    def timed(fn, n):
+        fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(n):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / n
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    fl = C.c_double(0.0)
+    t_m = timed(lambda: B.check(B.ptdp_ceiling_mfma(sink.data_ptr(), 256 * 4, 20000, C.byref(fl), sh), "ceiling_mfma"), 3)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev); dst = torch.empty_like(src)
+    t_c = timed(lambda: B.check(B.ptdp_ceiling_copy(src.data_ptr(), dst.data_ptr(), src.numel(), sh), "ceiling_copy"), 5)
+    ceilings = {"mfma_bf16_register_loop_tflops": round(fl.value / t_m / 1e12, 1),
+                "copy_1gib_read_plus_write_gbs": round(2 * src.numel() / t_c / 1e9, 1)}
+    del src, dst
+
     # ---- CPU oracle on a bounded sample of the same workload ------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -239,7 +259,7 @@ def main():
                    "dropout_p": 0.1, "model_flops_per_step": flops_step, "flop_factor": flop_factor,
                    "recompute_segment_layers": seg, "stage": args.stage, "activation_pool_gb": round(pool.numel() / 2 ** 30, 3),
                    "resident_hbm_gb": round(peak_hbm_bytes / 2 ** 30, 2)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu, "measured_ceilings": ceilings, "kernels": kernels,
         "context": "paper: 163 TFLOP/s per A100 = 52% of peak, end-to-end on 3072 GPUs, recompute counted (x4)",
     }
     print(json.dumps(out))

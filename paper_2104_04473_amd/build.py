@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libptdp.so")
-SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "lm_stage.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "lm_stage.hip", "ceilings.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

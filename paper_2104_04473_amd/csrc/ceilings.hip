@@ -1,0 +1,62 @@
+// Measured ceilings of the machine, for reading roofline fractions against something the chip was seen
+// to do: a register-resident MFMA loop (no memory traffic at all) and a plain 16-byte-per-lane copy.
+#include "common.h"
+
+namespace ptdp {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+// 8 waves per workgroup, 8 independent 32x32 accumulators per wave, operands never change.
+__global__ void __launch_bounds__(512) mfma_ceiling_kernel(float* sink, int iters) {
+  bf16x8_t a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
+    b[i] = (__bf16)(float)((threadIdx.x * 3 + i) & 1);
+  }
+  f32x16_t acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[j][r];
+  if (s == 123.456f) sink[0] = s;   // keeps the loop alive without a store on the usual path
+}
+
+__global__ void __launch_bounds__(256) copy_ceiling_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+}  // namespace ptdp
+
+using namespace ptdp;
+
+extern "C" {
+
+int ptdp_ceiling_mfma(float* sink, int workgroups, int iters, double* flops, void* stream) {
+  if (!sink || !flops) return PTDP_E_NULL_PTR;
+  if (workgroups <= 0 || iters <= 0) return PTDP_E_INVALID_ARG;
+  *flops = 2.0 * 32 * 32 * 16 * 8.0 * iters * 8.0 * workgroups;
+  hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)stream, sink, iters);
+  return hipGetLastError() == hipSuccess ? PTDP_OK : PTDP_E_HIP;
+}
+
+int ptdp_ceiling_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst) return PTDP_E_NULL_PTR;
+  if (bytes % 16 != 0 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return PTDP_E_INVALID_ARG;
+  if (bytes == 0) return PTDP_OK;
+  hipLaunchKernelGGL(copy_ceiling_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst,
+                     bytes / 16);
+  return hipGetLastError() == hipSuccess ? PTDP_OK : PTDP_E_HIP;
+}
+
+}  // extern "C"
