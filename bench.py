@@ -237,10 +237,12 @@ def main():
         return e0.elapsed_time(e1) * 1e-3 / n
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
     fl = C.c_double(0.0)
-    t_m = timed(lambda: B.check(B.ptdp_ceiling_mfma(sink.data_ptr(), 256 * 4, 20000, C.byref(fl), sh), "ceiling_mfma"), 3)
+    t_m = timed(lambda: B.check(B.ptdp_ceiling_mfma(sink.data_ptr(), 256 * 4, 20000, 0, C.byref(fl), sh), "ceiling_mfma"), 3)
+    t_r = timed(lambda: B.check(B.ptdp_ceiling_mfma(sink.data_ptr(), 256 * 4, 20000, 1, C.byref(fl), sh), "ceiling_mfma"), 3)
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev); dst = torch.empty_like(src)
     t_c = timed(lambda: B.check(B.ptdp_ceiling_copy(src.data_ptr(), dst.data_ptr(), src.numel(), sh), "ceiling_copy"), 5)
     ceilings = {"mfma_bf16_register_loop_tflops": round(fl.value / t_m / 1e12, 1),
+                "mfma_bf16_register_loop_random_operands_tflops": round(fl.value / t_r / 1e12, 1),
                 "copy_1gib_read_plus_write_gbs": round(2 * src.numel() / t_c / 1e9, 1)}
     del src, dst
 

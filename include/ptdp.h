@@ -382,11 +382,14 @@ int ptdp_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse,
 /* ---------------------------------------------------------------- ceilings */
 /* What the chip is seen to do, for reading roofline fractions: a loop of
  * v_mfma_f32_32x32x16_bf16 on registers only (workgroups x 8 waves x 8
- * accumulators x iters instructions; *flops (host) receives the FLOP count of
- * the launch; sink: dev, >= 4 bytes, not written in practice), and a copy of
+ * accumulators x iters instructions; random_operands 0: small constant
+ * integers, 1: hash-derived values spread like N(0,1), rotated between
+ * instructions as in a GEMM (more toggling bits, lower sustained clock);
+ * *flops (host) receives the FLOP count of the launch; sink: dev, >= 4 bytes,
+ * not written in practice), and a copy of
  * `bytes` (multiple of 16, 16-byte aligned pointers) with 16 bytes per lane.
  * The caller times them with events on `stream`. */
-int ptdp_ceiling_mfma(float* sink, int workgroups, int iters, double* flops, void* stream);
+int ptdp_ceiling_mfma(float* sink, int workgroups, int iters, int random_operands, double* flops, void* stream);
 int ptdp_ceiling_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 /* ---------------------------------------------------------------- profiling */

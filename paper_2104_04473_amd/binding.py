@@ -113,7 +113,7 @@ SIGNATURES = {
     "ptdp_attn_masked_fwd": (_i, [_i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "ptdp_attn_masked_bwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "ptdp_chunk_set_mask": (_i, [_vp, _vp]),
-    "ptdp_ceiling_mfma": (_i, [_vp, _i, _i, C.POINTER(C.c_double), _vp]),
+    "ptdp_ceiling_mfma": (_i, [_vp, _i, _i, _i, C.POINTER(C.c_double), _vp]),
     "ptdp_ceiling_copy": (_i, [_vp, _vp, _sz, _vp]),
     "ptdp_prof_enable": (_i, [_i]),
     "ptdp_prof_collect": (_i, [C.POINTER(ProfEntry)]),

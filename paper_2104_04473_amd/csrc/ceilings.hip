@@ -7,14 +7,28 @@ namespace ptdp {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
-// 8 waves per workgroup, 8 independent 32x32 accumulators per wave, operands never change.
+// 8 waves per workgroup, 8 independent 32x32 accumulators per wave.  RANDOM = false: two operand
+// registers of small integers that never change (few toggling bits).  RANDOM = true: four A and four B
+// operand sets of hash-derived values spread like N(0,1) samples in bf16, rotated so that consecutive
+// instructions see different operands, as in a real GEMM.
+template <bool RANDOM>
 __global__ void __launch_bounds__(512) mfma_ceiling_kernel(float* sink, int iters) {
-  bf16x8_t a, b;
+  bf16x8_t a[4], b[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (__bf16)(float)((threadIdx.x + i) & 3);
-    b[i] = (__bf16)(float)((threadIdx.x * 3 + i) & 1);
-  }
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (RANDOM) {
+        const uint64_t r = mix64(kGolden * (uint64_t)(((blockIdx.x * 512 + threadIdx.x) * 4 + s) * 8 + i + 1));
+        // sum of four 16-bit uniforms, centred: roughly normal with unit-order spread
+        const float u = (float)(r & 0xffff) + (float)((r >> 16) & 0xffff) + (float)((r >> 32) & 0xffff) + (float)(r >> 48);
+        a[s][i] = (__bf16)((u - 131070.f) * (1.f / 37837.f));
+        b[s][i] = (__bf16)((float)((r >> 7) & 0xffff) * (1.f / 18918.f) - 1.732f);
+      } else {
+        a[s][i] = (__bf16)(float)((threadIdx.x + i) & 3);
+        b[s][i] = (__bf16)(float)((threadIdx.x * 3 + i) & 1);
+      }
+    }
   f32x16_t acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j)
@@ -22,7 +36,8 @@ __global__ void __launch_bounds__(512) mfma_ceiling_kernel(float* sink, int iter
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    for (int j = 0; j < 8; ++j)
+      acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[RANDOM ? (j & 3) : 0], b[RANDOM ? ((j >> 1) & 3) : 0], acc[j], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
@@ -42,11 +57,14 @@ using namespace ptdp;
 
 extern "C" {
 
-int ptdp_ceiling_mfma(float* sink, int workgroups, int iters, double* flops, void* stream) {
+int ptdp_ceiling_mfma(float* sink, int workgroups, int iters, int random_operands, double* flops, void* stream) {
   if (!sink || !flops) return PTDP_E_NULL_PTR;
   if (workgroups <= 0 || iters <= 0) return PTDP_E_INVALID_ARG;
   *flops = 2.0 * 32 * 32 * 16 * 8.0 * iters * 8.0 * workgroups;
-  hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)stream, sink, iters);
+  if (random_operands)
+    hipLaunchKernelGGL(mfma_ceiling_kernel<true>, dim3(workgroups), dim3(512), 0, (hipStream_t)stream, sink, iters);
+  else
+    hipLaunchKernelGGL(mfma_ceiling_kernel<false>, dim3(workgroups), dim3(512), 0, (hipStream_t)stream, sink, iters);
   return hipGetLastError() == hipSuccess ? PTDP_OK : PTDP_E_HIP;
 }
 
