@@ -38,6 +38,10 @@
  *    optimizer steps only at the pipeline flush (section 2.2).
  *  - Device buffers must be 16-byte aligned; h, hp, fp and dh must be
  *    multiples of 8.
+ *  - A ptdp_chunk may be used by one thread at a time; different chunks may be
+ *    used from different threads (on streams of the device that is current in
+ *    the calling thread).  Calls that share a workspace or stash must be
+ *    ordered on one stream.
  */
 #ifndef PTDP_H
 #define PTDP_H
@@ -398,7 +402,9 @@ int ptdp_ceiling_copy(const void* src, void* dst, size_t bytes, void* stream);
  * (this serialises nothing but adds a few microseconds per launch, so
  * whole-step throughput is measured with profiling disabled).
  * ptdp_prof_collect synchronises the recorded events and adds their elapsed
- * times to per-family totals. */
+ * times to per-family totals.  The profiling state is process-wide and not
+ * thread-safe: enable it from one thread, on one device, while no other
+ * thread calls the library. */
 enum {
   PTDP_K_GEMM_NN = 0, PTDP_K_GEMM_NT, PTDP_K_GEMM_TN, PTDP_K_ATTN_FWD, PTDP_K_ATTN_BWD,
   PTDP_K_LN_FWD, PTDP_K_LN_BWD, PTDP_K_GELU_FWD, PTDP_K_GELU_BWD, PTDP_K_BDA_FWD, PTDP_K_BDA_BWD,

@@ -804,13 +804,8 @@ template <int DH, bool CAUSAL>
 static int attn_fwd_mfma_t(const bf16_t* qkv, bf16_t* ctx, float* lse, int s, int b, int heads, const uint8_t* mask,
                            hipStream_t stream) {
   constexpr int smem = 2 * TileGeom<DH>::BYTES;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_mfma<DH, CAUSAL>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-      return PTDP_E_HIP;
-    attr_set = true;
-  }
+  static bool done[kMaxDevices] = {};
+  if (set_dynamic_smem(reinterpret_cast<const void*>(attn_fwd_mfma<DH, CAUSAL>), smem, done) != PTDP_OK) return PTDP_E_HIP;
   const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
   hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL>), grid, dim3(kAttnThreads), smem, stream, qkv, ctx, lse, s, b, heads, mask);
   return PTDP_OK;
@@ -862,15 +857,10 @@ static int attn_bwd_mfma_t(const bf16_t* qkv, const bf16_t* ctx, const float* ls
                            float* delta, int s, int b, int heads, const uint8_t* mask, hipStream_t stream) {
   constexpr int smem_dq = 2 * TileGeom<DH>::BYTES;
   constexpr int smem_dkv = 2 * TileGeom<DH>::BYTES + 2 * kBKV * (int)sizeof(float) + (CAUSAL ? 0 : kBQ * kMaskLdsStride);
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dq_mfma<DH, CAUSAL>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem_dq) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH, CAUSAL>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem_dkv) != hipSuccess)
-      return PTDP_E_HIP;
-    attr_set = true;
-  }
+  static bool done_dq[kMaxDevices] = {}, done_dkv[kMaxDevices] = {};
+  if (set_dynamic_smem(reinterpret_cast<const void*>(attn_bwd_dq_mfma<DH, CAUSAL>), smem_dq, done_dq) != PTDP_OK ||
+      set_dynamic_smem(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH, CAUSAL>), smem_dkv, done_dkv) != PTDP_OK)
+    return PTDP_E_HIP;
   const size_t nrows = (size_t)s * b * heads;
   hipLaunchKernelGGL(attn_delta_bf16, dim3((unsigned)((nrows + 3) / 4)), dim3(256), 0, stream, ctx, dctx, delta, s, b,
                      heads, DH);

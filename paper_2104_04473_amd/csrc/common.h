@@ -111,6 +111,21 @@ struct Launch {
   bool closed_;
 };
 
+// Per-device one-time state (function attributes, device properties): each device of the process keeps its own.
+constexpr int kMaxDevices = 64;
+inline int device_slot() {
+  int d = 0;
+  return (hipGetDevice(&d) == hipSuccess && d >= 0 && d < kMaxDevices) ? d : -1;
+}
+// Raises a kernel's dynamic shared memory limit once per device; `done` is that kernel's flag array.
+inline int set_dynamic_smem(const void* kern, int bytes, bool (&done)[kMaxDevices]) {
+  const int d = device_slot();
+  if (d >= 0 && done[d]) return PTDP_OK;
+  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return PTDP_E_HIP;
+  if (d >= 0) done[d] = true;
+  return PTDP_OK;
+}
+
 // kernels (defined in the .hip files; all arguments validated by the callers in api.cpp)
 int launch_layernorm_fwd(int dtype, const void* x, const void* gain, const void* bias, void* u, float* mu,
                          float* rstd, void* x_copy, int rows, int width, float eps, hipStream_t st);

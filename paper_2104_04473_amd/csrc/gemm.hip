@@ -444,20 +444,11 @@ gemm_sk_reduce_kernel(const float* __restrict__ slabs, void* Cv, const bf16_t* _
 
 constexpr int kWGM = 2, kWGN = 4, kGemmThreads = kWGM * kWGN * 64, kGemmSmem = 2 * kStageBytes;
 
-template <typename Kern> static int set_smem_once(Kern kern, bool* done) {
-  if (*done) return PTDP_OK;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmSmem) !=
-      hipSuccess)
-    return PTDP_E_HIP;
-  *done = true;
-  return PTDP_OK;
-}
-
 template <bool TA, bool TB, int OUT>
 static int launch_dp(const GemmArgs& g, void* C, hipStream_t st) {
   auto kern = gemm_bf16_dp_kernel<TA, TB, OUT, kWGM, kWGN>;
-  static bool done = false;
-  if (set_smem_once(kern, &done) != PTDP_OK) return PTDP_E_HIP;
+  static bool done[kMaxDevices] = {};
+  if (set_dynamic_smem(reinterpret_cast<const void*>(kern), kGemmSmem, done) != PTDP_OK) return PTDP_E_HIP;
   const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
   const int blocks = 8 * tiles_m * ((tiles_n + 7) / 8);  // 8 XCD queues of equal length; surplus blocks exit at once
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, C);
@@ -467,21 +458,22 @@ static int launch_dp(const GemmArgs& g, void* C, hipStream_t st) {
 template <bool TA, bool TB>
 static int launch_sk(const GemmArgs& g, float* slabs, int blocks, hipStream_t st) {
   auto kern = gemm_bf16_sk_kernel<TA, TB, kWGM, kWGN>;
-  static bool done = false;
-  if (set_smem_once(kern, &done) != PTDP_OK) return PTDP_E_HIP;
+  static bool done[kMaxDevices] = {};
+  if (set_dynamic_smem(reinterpret_cast<const void*>(kern), kGemmSmem, done) != PTDP_OK) return PTDP_E_HIP;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, slabs);
   return PTDP_OK;
 }
 
 static int compute_units() {
-  static int n = 0;
-  if (n == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
-    n = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  }
-  return n;
+  static int n[kMaxDevices] = {};
+  const int d = device_slot();
+  if (d >= 0 && n[d] > 0) return n[d];
+  hipDeviceProp_t prop;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
+  const int cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  if (d >= 0) n[d] = cu;
+  return cu;
 }
 
 size_t gemm_workspace_bytes() { return (size_t)compute_units() * 2 * kSlabFloats * sizeof(float); }
