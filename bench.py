@@ -186,13 +186,19 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # recorded, never waited on
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record(stream)
+    for i in range(args.steps):
         step()
+        marks[i + 1].record(stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = 1e3 * dt / args.steps
     tflops = flops_step * args.steps / dt / 1e12
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    step_ms = {"median": round(per_step[len(per_step) // 2], 3), "min": round(per_step[0], 3),
+               "max": round(per_step[-1], 3)}
 
     # ---- per-kernel pass: HIP event pairs on the launch stream around every launch ------------------
     B.ptdp_prof_enable(1)
@@ -253,7 +259,7 @@ def main():
 
     out = {
         "metric": "model_tflops_per_gpu_fwd_bwd" + ("_recompute" if seg else "") + ("" if args.stage == "middle" else "_%s_stage" % args.stage), "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "step_ms": step_ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "config": {"workload": "%s: %s" % (args.workload, w["desc"]), "h": w["h"], "a": w["a"], "t": w["t"],
