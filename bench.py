@@ -2,18 +2,21 @@
 """Benchmark of the per-GPU PTD-P compute path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c3|c2|c5] [--no-cpu-baseline]
+                    [--recompute SEG] [--stage middle|first|last]
 
 A step is one pass of the whole hot path over one microbatch of synthetic input: forward of every
 layer of the stage shard, then backward of every layer (for c5: the whole interleaved 1F1B order of
 one device, 2 chunks x 8 microbatches).  Inputs, parameters, gradient accumulators, stash and
 workspace are resident in HBM before the timed region.  Prints ONE JSON line.
 
-value       model TFLOP/s = 3 x (24 b s h^2 + 4 b s^2 h)/t per layer and microbatch (paper appendix; no
-            recompute forward is executed, so the paper's factor 4 is not used) / wall time
+value       model TFLOP/s = 3 x (24 b s h^2 + 4 b s^2 h)/t per layer and microbatch (paper appendix) / wall
+            time.  The paper's factor 4 is used only with --recompute, where the rerun forward is really
+            executed; --stage last adds the logit layer's 6 b s h V / t.  Both carry their own metric name.
 roofline    the GEMM family with the largest share of the step, timed live with HIP events on the
             launch stream in a second pass over the same steps (event pairs around every launch)
 cpu_baseline the fp64 numpy oracle, one layer forward+backward at the workload's shape on a bounded
             number of sequence positions, on the host cores of this machine
+measured_ceilings  a register-resident MFMA loop (constant and random operands) and a 1 GiB copy
 """
 import argparse
 import ctypes as C
