@@ -135,3 +135,59 @@ def test_schedule_run_interleaved():
     Ps = [params_np(P) for P in rigs[1].params]
     wy, _ = L.chunk_forward(np64(xin[1 * m + 2]), Ps, ocfg, 2 * (1 * p + rank), 2)
     assert_close(np64(yout[1 * m + 2]), wy, cfg.dtype, "y of (chunk 1, microbatch 2)")
+
+
+def test_chunk_forward_backward_replays_from_a_hip_graph():
+    """The library allocates nothing, clears nothing with memsets and never synchronises, so a step can be
+    captured into a HIP graph.  Every replay (with eager work and synchronisations in between) must give the
+    bits of the eager step, including the += into the gradient buffers."""
+    cfg = B.make_cfg(h=256, a=4, t=1, s=64, b=2, dtype=B.BF16, p_hidden=0.1, seed=6)
+    rig = LayerRig(cfg, 2, first_layer=0, seed=90)
+    shape = (cfg.s, cfg.b, cfg.h)
+    x = randn(shape, cfg.dtype, 1); dy = randn(shape, cfg.dtype, 2)
+    y = torch.empty_like(x); dx = torch.empty_like(x)
+
+    def step():
+        B.check(rig.chunk.forward(1, x.data_ptr(), y.data_ptr(), rig.stash.data_ptr(), rig.ws.data_ptr()), "fwd")
+        B.check(rig.chunk.backward(1, dy.data_ptr(), dx.data_ptr(), rig.stash.data_ptr(), rig.ws.data_ptr()), "bwd")
+
+    step()                      # eager reference (also sets the kernels' one-time attributes before capture)
+    sync()
+    y_ref, dx_ref = y.clone(), dx.clone()
+    g1 = [{k: v.clone() for k, v in G.items()} for G in rig.grads]       # gradients after one step
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()                  # captured on the capture stream (torch's current stream inside the context)
+    sync()
+    for G in rig.grads:
+        for v in G.values():
+            v.zero_()
+    for replay in range(1, 4):
+        y.zero_(); dx.zero_()
+        graph.replay()
+        sync()
+        assert torch.equal(y, y_ref) and torch.equal(dx, dx_ref), "replay %d" % replay
+        scratch = randn(shape, cfg.dtype, 10 + replay) * 2.0            # unrelated eager work between replays
+        sync()
+        del scratch
+        if replay == 1:
+            for l in range(2):
+                for k in B.PARAM_NAMES:
+                    assert torch.equal(rig.grads[l][k], g1[l][k]), (l, k)
+    # three replays accumulated three times the same addend, in the order an eager loop would
+    for G in rig.grads:
+        for v in G.values():
+            v.zero_()
+    for _ in range(3):
+        step()
+    sync()
+    eager3 = [{k: v.clone() for k, v in G.items()} for G in rig.grads]
+    for G in rig.grads:
+        for v in G.values():
+            v.zero_()
+    for _ in range(3):
+        graph.replay()
+    sync()
+    for l in range(2):
+        for k in B.PARAM_NAMES:
+            assert torch.equal(rig.grads[l][k], eager3[l][k]), (l, k)
