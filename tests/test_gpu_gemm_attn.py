@@ -9,7 +9,8 @@ from gpu_util import assert_close, np64, randn, stream, sync, tdt
 
 pytestmark = pytest.mark.gpu
 
-SHAPES = [(8, 8, 8), (136, 264, 72), (256, 256, 64), (520, 776, 200), (1032, 264, 1096), (264, 1032, 520)]
+SHAPES = [(8, 8, 8), (136, 264, 72), (256, 256, 64), (520, 776, 200), (1032, 264, 1096), (264, 1032, 520),
+          (264, 136, 128), (72, 520, 136), (136, 72, 192)]     # 1, 2, 3 and more k-steps, whole and ragged
 
 
 @pytest.mark.parametrize("dtype", [B.F32, B.BF16])
