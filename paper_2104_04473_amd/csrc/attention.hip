@@ -1,4 +1,4 @@
-// Fused causal self-attention of one tensor-parallel shard (paper section 2.3: heads split over the
+// Fused self-attention of one tensor-parallel shard (implicit causal mask, or a general byte mask) (paper section 2.3: heads split over the
 // ranks; section 4.2: scale + implicit causal mask + softmax fused; here the two batched GEMMs
 // Q K^T and P V of the appendix are fused in as well, so the s x s matrix never reaches HBM).
 //
@@ -8,8 +8,7 @@
 // bf16 forward: S^T = K Q^T and O^T = V^T P^T on v_mfma_f32_32x32x16_bf16, so that the softmax
 // probabilities leave the first MFMA already in the register layout the second one wants as its
 // B operand.  One wave owns 32 queries; a block of 2 waves shares 64-key K and V tiles in LDS.
-// The "rowwise" kernels are the plain formulation (one wave per row): they are the fp32 path and the
-// reference-shaped fallback of the bf16 backward.
+// The "rowwise" kernels are the plain formulation (one wave per row): they are the fp32 path.
 #include "common.h"
 
 namespace ptdp {

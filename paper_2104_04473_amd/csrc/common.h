@@ -126,7 +126,7 @@ inline int set_dynamic_smem(const void* kern, int bytes, bool (&done)[kMaxDevice
   return PTDP_OK;
 }
 
-// kernels (defined in the .hip files; all arguments validated by the callers in api.cpp)
+// kernels (defined in the .hip files; all arguments validated by the callers in api.hip)
 int launch_layernorm_fwd(int dtype, const void* x, const void* gain, const void* bias, void* u, float* mu,
                          float* rstd, void* x_copy, int rows, int width, float eps, hipStream_t st);
 int launch_layernorm_bwd(int dtype, const void* du, const void* x, const void* gain, const float* mu,
