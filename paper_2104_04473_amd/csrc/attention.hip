@@ -1,6 +1,7 @@
-// Fused self-attention of one tensor-parallel shard (implicit causal mask, or a general byte mask) (paper section 2.3: heads split over the
-// ranks; section 4.2: scale + implicit causal mask + softmax fused; here the two batched GEMMs
-// Q K^T and P V of the appendix are fused in as well, so the s x s matrix never reaches HBM).
+// Fused self-attention of one tensor-parallel shard (paper section 2.3: heads split over the ranks;
+// section 4.2: scale + mask + softmax fused, with the implicit causal mask or a general byte mask;
+// here the two batched GEMMs Q K^T and P V of the appendix are fused in as well, so the s x s matrix
+// never reaches HBM).
 //
 // qkv is [s, b, 3*hp] with columns [Q heads | K heads | V heads]; for sample j and local head e the
 // row of token i starts at qkv + (i*b + j)*3*hp + {0, hp, 2hp} + e*dh.
