@@ -344,22 +344,25 @@ int ptdp_layer_backward(ptdp_chunk* ch, int layer, int64_t microbatch, const voi
   PTDP_TRY(launch_bda_bwd(dt, dy, wf(WS_H1), G.b_2, cs, T, h, c.p_hidden,
                           dropout_key(c.seed, gl, 1, (uint64_t)microbatch), st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_2, wf(WS_BIG), nullptr, T, fp, h, 0, 0, sk, skb, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_G), wf(WS_H1), G.w_2, nullptr, fp, h, T, 1, 1, sk, skb, st));
+  // (the weight gradient of w_2 waits for that of w_1: the two run as one launch, so that the second one's
+  // tiles fill the last, partial round of the first; its inputs G and WS_H1 stay untouched until then)
   PTDP_TRY(launch_bias_gelu_bwd(dt, c.gelu_mode, wf(WS_BIG), sf(PTDP_STASH_Z), P.b_1, wf(WS_BIG), G.b_1, cs, T, fp, st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_BIG), P.w_1, wf(WS_H2), nullptr, T, h, fp, 0, 0, sk, skb, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_U2), wf(WS_BIG), G.w_1, nullptr, h, fp, T, 1, 1, sk, skb, st));
+  PTDP_TRY(launch_gemm_tn_pair(dt, sf(PTDP_STASH_G), wf(WS_H1), G.w_2, fp, h, sf(PTDP_STASH_U2), wf(WS_BIG), G.w_1, h, fp,
+                               T, st));
   PTDP_TRY(launch_layernorm_bwd(dt, wf(WS_H2), sf(PTDP_STASH_X1), P.ln2_g, (const float*)sf(PTDP_STASH_MU2),
                                 (const float*)sf(PTDP_STASH_RSTD2), dy, wf(WS_X1), G.ln2_g, G.ln2_b, cs, T, h, st));
   // attention block
   PTDP_TRY(launch_bda_bwd(dt, wf(WS_X1), wf(WS_H1), G.b_o, cs, T, h, c.p_hidden,
                           dropout_key(c.seed, gl, 0, (uint64_t)microbatch), st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_o, wf(WS_CTX), nullptr, T, hp, h, 0, 0, sk, skb, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_CTX), wf(WS_H1), G.w_o, nullptr, hp, h, T, 1, 1, sk, skb, st));
+  // (w_o's weight gradient runs paired with w_qkv's below; CTX and WS_H1 stay untouched until then)
   PTDP_TRY(launch_attn_bwd(dt, sf(PTDP_STASH_QKV), sf(PTDP_STASH_CTX), (const float*)sf(PTDP_STASH_LSE), wf(WS_CTX),
                            wf(WS_QKV), (float*)wf(WS_DELTA), c.s, c.b, (int)d.al, (int)d.dh, ch->mask, c.causal, st));
   PTDP_TRY(launch_colsum(dt, wf(WS_QKV), G.b_qkv, cs, T, 3 * hp, st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_QKV), P.w_qkv, wf(WS_H2), nullptr, T, h, 3 * hp, 0, 0, sk, skb, st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_TN, sf(PTDP_STASH_U), wf(WS_QKV), G.w_qkv, nullptr, h, 3 * hp, T, 1, 1, sk, skb, st));
+  PTDP_TRY(launch_gemm_tn_pair(dt, sf(PTDP_STASH_U), wf(WS_QKV), G.w_qkv, h, 3 * hp, sf(PTDP_STASH_CTX), wf(WS_H1), G.w_o, hp,
+                               h, T, st));
   PTDP_TRY(launch_layernorm_bwd(dt, wf(WS_H2), sf(PTDP_STASH_X), P.ln1_g, (const float*)sf(PTDP_STASH_MU1),
                                 (const float*)sf(PTDP_STASH_RSTD1), wf(WS_X1), dx, G.ln1_g, G.ln1_b, cs, T, h, st));
   return PTDP_OK;

@@ -334,16 +334,14 @@ template <int TM, int TN> __device__ __forceinline__ void zero_acc(f32x16_t (&ac
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 }
 
-// One workgroup per output tile ("data-parallel" form).
+// One workgroup per output tile ("data-parallel" form); `id` is the workgroup's index inside its problem.
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Each XCD owns the column
+// tiles x, x+8, ... and works through them in groups of up to 8 row tiles, so that the
+// workgroups resident on one XCD share 8 A panels and 4 B panels through that L2.
 template <bool TA, bool TB, int OUT, int WGM, int WGN>
-__global__ void __launch_bounds__(WGM * WGN * 64)
-gemm_bf16_dp_kernel(GemmArgs g, void* Cv) {
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
-  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Each XCD owns the column
-  // tiles x, x+8, ... and works through them in groups of up to 8 row tiles, so that the
-  // workgroups resident on one XCD share 8 A panels and 4 B panels through that L2.
+__device__ __forceinline__ void gemm_dp_tile(const GemmArgs& g, void* Cv, int id, char* smem) {
   const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int xcd = id & 7, local = id >> 3;
   const int nx = (tiles_n + 7) / 8;                 // column tiles per XCD (some may be past the end)
   const int per_group = 8 * nx;                     // blocks of one full group of 8 row tiles
   const int grp = local / per_group, in_grp = local % per_group;
@@ -354,6 +352,28 @@ gemm_bf16_dp_kernel(GemmArgs g, void* Cv) {
   zero_acc(acc);
   gemm_mainloop<TA, TB, WGM, WGN>(acc, g, tile_m * kBM, tile_n * kBN, 0, (g.K + BK - 1) / BK, smem);
   gemm_epilogue<OUT, WGM, WGN>(acc, Cv, g.ldc, g.bias, g.M, g.N, tile_m * kBM, tile_n * kBN, smem);
+}
+// workgroups of one problem (a multiple of 8, so that a second problem starts on XCD 0 again)
+static inline int dp_blocks(const GemmArgs& g) {
+  const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
+  return 8 * tiles_m * ((tiles_n + 7) / 8);  // 8 XCD queues of equal length; surplus workgroups exit at once
+}
+
+template <bool TA, bool TB, int OUT, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64)
+gemm_bf16_dp_kernel(GemmArgs g, void* Cv) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  gemm_dp_tile<TA, TB, OUT, WGM, WGN>(g, Cv, blockIdx.x, smem);
+}
+
+// Two independent problems of the same form in one launch: the second one's workgroups fill the CUs that
+// the first one's last, partial round of tiles would leave idle.  n0 = dp_blocks(g0).
+template <bool TA, bool TB, int OUT, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64)
+gemm_bf16_dp_pair_kernel(GemmArgs g0, void* C0, GemmArgs g1, void* C1, int n0) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  if ((int)blockIdx.x < n0) gemm_dp_tile<TA, TB, OUT, WGM, WGN>(g0, C0, blockIdx.x, smem);
+  else gemm_dp_tile<TA, TB, OUT, WGM, WGN>(g1, C1, blockIdx.x - n0, smem);
 }
 
 // "Stream-K" form for a tile count that does not fill the machine evenly: the (tile, k-tile) iteration
@@ -449,9 +469,7 @@ static int launch_dp(const GemmArgs& g, void* C, hipStream_t st) {
   auto kern = gemm_bf16_dp_kernel<TA, TB, OUT, kWGM, kWGN>;
   static bool done[kMaxDevices] = {};
   if (set_dynamic_smem(reinterpret_cast<const void*>(kern), kGemmSmem, done) != PTDP_OK) return PTDP_E_HIP;
-  const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
-  const int blocks = 8 * tiles_m * ((tiles_n + 7) / 8);  // 8 XCD queues of equal length; surplus blocks exit at once
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, C);
+  hipLaunchKernelGGL(kern, dim3(dp_blocks(g)), dim3(kGemmThreads), kGemmSmem, st, g, C);
   return PTDP_OK;
 }
 
@@ -536,6 +554,41 @@ static int launch_bf16_mode(const void* A, const void* B, void* C, const void* b
                          (void*)((bf16_t*)C + n_dp), bias ? (const bf16_t*)bias + n_dp : nullptr, M, r.N, K, (size_t)N, ncu);
   }
   return PTDP_OK;
+}
+
+static GemmArgs tn_args(const void* A, const void* B, int M, int N, int K) {
+  GemmArgs g;
+  g.A = (const bf16_t*)A;
+  g.B = (const bf16_t*)B;
+  g.bias = nullptr;
+  g.a_end = (const char*)A + (size_t)M * K * 2;
+  g.b_end = (const char*)B + (size_t)N * K * 2;
+  g.M = M; g.N = N; g.K = K;
+  g.lda = (size_t)M;
+  g.ldb = (size_t)N;
+  g.ldc = (size_t)N;
+  return g;
+}
+
+// C0[M0,N0] += A0^T B0 and C1[M1,N1] += A1^T B1 (fp32 C, both operands [K, .]), sharing K: two weight
+// gradients whose inputs are ready at the same time.  In bf16 they run as one launch.
+int launch_gemm_tn_pair(int dtype, const void* A0, const void* B0, float* C0, int M0, int N0, const void* A1,
+                        const void* B1, float* C1, int M1, int N1, int K, hipStream_t st) {
+  if (dtype == PTDP_F32 || M0 == 0 || N0 == 0 || M1 == 0 || N1 == 0 ||
+      (size_t)M0 * K * 2 >= 0x7fffffffull || (size_t)N0 * K * 2 >= 0x7fffffffull ||
+      (size_t)M1 * K * 2 >= 0x7fffffffull || (size_t)N1 * K * 2 >= 0x7fffffffull) {
+    const int rc = launch_gemm(dtype, PTDP_GEMM_TN, A0, B0, C0, nullptr, M0, N0, K, 1, 1, nullptr, 0, st);
+    if (rc != PTDP_OK) return rc;
+    return launch_gemm(dtype, PTDP_GEMM_TN, A1, B1, C1, nullptr, M1, N1, K, 1, 1, nullptr, 0, st);
+  }
+  Launch L(PTDP_K_GEMM_TN, 2.0 * K * ((double)M0 * N0 + (double)M1 * N1), st);
+  const GemmArgs g0 = tn_args(A0, B0, M0, N0, K), g1 = tn_args(A1, B1, M1, N1, K);
+  auto kern = gemm_bf16_dp_pair_kernel<true, true, OUT_F32_RMW, kWGM, kWGN>;
+  static bool done[kMaxDevices] = {};
+  if (set_dynamic_smem(reinterpret_cast<const void*>(kern), kGemmSmem, done) != PTDP_OK) return PTDP_E_HIP;
+  const int n0 = dp_blocks(g0);
+  hipLaunchKernelGGL(kern, dim3(n0 + dp_blocks(g1)), dim3(kGemmThreads), kGemmSmem, st, g0, (void*)C0, g1, (void*)C1, n0);
+  return L.status();
 }
 
 int launch_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N, int K,
