@@ -252,6 +252,17 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kB
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bfr[c][j], acc[i][j], 0, 0, 0);
+      // Scheduling hint: spread this step's LDS reads between its MFMAs instead of ahead of them (measured:
+      // +2..5 % with two 16-byte reads per two MFMAs when both operands are k-contiguous, +1 % one to one
+      // when B needs transposing reads, nothing when both do).
+      if (!TA) {
+        constexpr int per = TB ? 1 : 2;
+#pragma unroll
+        for (int q = 0; q < TM * TN / per; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, per, 0);   // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, per, 0);   // LDS read
+        }
+      }
     }
   }
 }
