@@ -10,9 +10,11 @@ HIP path: both sides restate the same definitions independently.
 Modules
 -------
 dropout_hash  counter-based dropout mask (integer, bit-exact on both sides)
-gpt_layer     forward / backward of one tensor-parallel shard of a GPT layer
-flops         the paper's closed forms (eq. 2, eq. 3, appendix, 8TP/nX)
+gpt_layer     forward / backward of one tensor-parallel shard of a GPT layer (causal or general mask)
+flops         the paper's closed forms (eq. 1, eq. 2, eq. 3, appendix, 8TP/nX)
 schedule      1F1B / interleaved 1F1B order of one device + p-device simulator
+recompute     activation recomputation: memory model of section 3.5, backward from checkpoints
+lm_stage      first / last stage extras: embeddings, final LayerNorm, logit layer, loss
 
 Parity status: every function here is pinned by ``tests/test_oracle_*.py``
 (finite differences, an independent autograd derivation, closed forms,
