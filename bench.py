@@ -14,8 +14,8 @@ value       model TFLOP/s = 3 x (24 b s h^2 + 4 b s^2 h)/t per layer and microba
             executed; --stage last adds the logit layer's 6 b s h V / t.  Both carry their own metric name.
 roofline    the GEMM family with the largest share of the step, timed live with HIP events on the
             launch stream in a second pass over the same steps (event pairs around every launch)
-cpu_baseline the fp64 numpy oracle, one layer forward+backward at the workload's shape on a bounded
-            number of sequence positions, on the host cores of this machine
+cpu_baseline the fp64 numpy oracle, one full layer forward+backward at the workload's shape (one of the
+            step's identical layer passes; about two minutes at c4), on the host cores of this machine
 measured_ceilings  a register-resident MFMA loop (constant and random operands) and a 1 GiB copy
 """
 import argparse
@@ -56,7 +56,8 @@ def main():
                          "(V=51200 split over t) and loss after them.  Not the default metric.")
     ap.add_argument("--pmc-calibrate", action="store_true",
                     help="first run a plain 1 GiB read + 1 GiB write kernel (scale reference for FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--cpu-sample-positions", type=int, default=0, help="sequence positions of the oracle sample")
+    ap.add_argument("--cpu-sample-positions", type=int, default=0,
+                    help="restrict the oracle sample to the first N sequence positions (default: the whole layer)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build covers one GPU's share of the work only (no collectives are built); "
@@ -291,8 +292,9 @@ def measured_traffic(workload, family):
 
 
 def cpu_baseline(w, params_dev, positions):
-    """Times the oracle (fp64 numpy, as it stands) on one layer forward+backward at the workload's
-    h, a, t, b, restricted to the first `positions` sequence positions."""
+    """Times the oracle (fp64 numpy, as it stands) on ONE full layer forward+backward of the workload (all s
+    positions; the workload's layers are identical in cost, so the whole step is `layers` times this), on the
+    host cores of this machine.  `positions` > 0 restricts the sample to the first `positions` sequence positions."""
     import numpy as np
     from oracle import gpt_layer as L
     from oracle import flops as F
@@ -301,24 +303,27 @@ def cpu_baseline(w, params_dev, positions):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    if positions <= 0:
-        # aim at roughly 10-30 s: ~3 x 24 b s h^2 / t FLOPs at O(100) GFLOP/s fp64
-        target = 1.5e12
-        per_pos = 3 * 24 * w["b"] * w["h"] ** 2 / w["t"]
-        positions = int(max(16, min(w["s"], target // per_pos)))
+    if positions <= 0 or positions > w["s"]:
+        positions = w["s"]
     cfg = L.LayerConfig(h=w["h"], a=w["a"], t=w["t"], s=positions, b=w["b"], p_hidden=0.1, seed=0)
     P = {k: v.float().cpu().numpy() for k, v in params_dev.items()}
     rng = np.random.default_rng(0)
     x = rng.standard_normal((positions, w["b"], w["h"]))
     dy = rng.standard_normal((positions, w["b"], w["h"]))
+    print("bench.py: timing the CPU oracle on one layer (%d positions, %d threads) ..." % (positions, cores),
+          file=sys.stderr, flush=True)
     t0 = time.perf_counter()
     y, cache = L.layer_forward(x, P, cfg, 0, 0)
+    print("bench.py: oracle forward done after %.0f s" % (time.perf_counter() - t0), file=sys.stderr, flush=True)
     dx, G = L.layer_backward(dy, P, cfg, cache)
     dt = time.perf_counter() - t0
     fl = F.shard_layer_flops(w["b"], positions, w["h"], w["t"])
+    n_layers = w["layers"] * w.get("chunks", 1) * w.get("m", 1)
+    whole = "all %d" % w["s"] if positions == w["s"] else "first %d of %d" % (positions, w["s"])
     return {"value": round(fl / dt / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "seconds": round(dt, 2),
-            "sample": "1 layer forward+backward, fp64 numpy, first %d of %d sequence positions, same h/a/t/b" % (positions, w["s"])}
+            "sample": "1 layer forward+backward of the step's %d layer passes (identical in cost: the whole step would "
+                      "take %d x %.0f s), fp64 numpy, %s sequence positions, same h/a/t/b" % (n_layers, n_layers, dt, whole)}
 
 
 if __name__ == "__main__":

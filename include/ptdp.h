@@ -136,6 +136,24 @@ size_t ptdp_stash_offset(const ptdp_layer_cfg* cfg, int field);
  * between calls; one workspace may serve every call on the same stream). */
 size_t ptdp_workspace_bytes(const ptdp_layer_cfg* cfg);
 
+/* Where ptdp_layer_backward leaves the intermediate gradients of the appendix's
+ * dgrad / wgrad products inside the workspace when it returns (valid until the
+ * next call that uses the workspace; storage dtype, row-major).  On a
+ * tensor-parallel shard these are also the buffers an all-reduce of section 2.3
+ * would act on (PTDP_WS_DU: the operator f of the attention block). */
+enum {
+  PTDP_WS_DO = 0,  /* grad of (o + b_o) = dx1 * mask_0 / (1-p)        [T, h]   */
+  PTDP_WS_DU,      /* grad of LayerNorm-1's output u                   [T, h]   */
+  PTDP_WS_DX1,     /* grad of x1 (after LayerNorm-2's backward)        [T, h]   */
+  PTDP_WS_CHAIN,   /* gradient handed from layer l+1 to layer l by ptdp_chunk_backward [T, h] */
+  PTDP_WS_DZ,      /* grad of (z + b_1)                                [T, fp]  */
+  PTDP_WS_DCTX,    /* grad of the attention output                     [T, hp]  */
+  PTDP_WS_DQKV,    /* grad of Q|K|V                                    [T, 3hp] */
+  PTDP_WS_NFIELDS
+};
+/* Byte offset of such a field in the workspace; (size_t)-1 on an invalid cfg or field. */
+size_t ptdp_workspace_offset(const ptdp_layer_cfg* cfg, int field);
+
 /* Model FLOPs of one layer's forward pass on this shard for one microbatch:
  * (24 b s h^2 + 4 b s^2 h) / t  (paper appendix; GEMMs only, full s x s
  * attention matrix).  Backward is counted as twice this.  -1 on invalid cfg. */
@@ -366,6 +384,16 @@ enum { PTDP_GEMM_NN = 0, PTDP_GEMM_NT = 1, PTDP_GEMM_TN = 2 };
 int ptdp_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N,
               int K, int out_f32, int accumulate, void* workspace, size_t workspace_bytes, void* stream);
 size_t ptdp_gemm_workspace_bytes(void);
+/* Host only (no device work): how ptdp_gemm splits a bf16 call (appendix: the
+ * GEMMs of a layer).  *dp_columns = columns of C computed one workgroup per
+ * 256 x 256 tile (a multiple of 256, or N); the remaining *sk_tiles tiles
+ * (always fewer than *sk_workgroups) have their (tile, 64-wide k-step) space cut
+ * into *sk_workgroups equal contiguous ranges, workgroup i taking
+ * [total*i/n, total*(i+1)/n) with tiles numbered row tile fastest.
+ * has_bias / workspace_bytes as in the call being planned.  Returns 0, or
+ * PTDP_E_INVALID_ARG / PTDP_E_NULL_PTR. */
+int ptdp_gemm_plan(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t workspace_bytes,
+                   int* dp_columns, int* sk_tiles, int* sk_workgroups);
 
 /* Fused causal attention over qkv [s, b, 3hp] (scale 1/sqrt(dh), implicit
  * causal mask, softmax, times V; section 4.2's scale+mask+softmax fusion

@@ -25,6 +25,7 @@ F32, BF16 = 0, 1
 GELU_ERF, GELU_TANH = 0, 1
 GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 STASH_FIELDS = ("X", "U", "QKV", "CTX", "X1", "U2", "Z", "G", "MU1", "RSTD1", "MU2", "RSTD2", "LSE")
+WS_FIELDS = ("DO", "DU", "DX1", "CHAIN", "DZ", "DCTX", "DQKV")
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
 PROF_FAMILIES = 15
 
@@ -71,6 +72,7 @@ SIGNATURES = {
     "ptdp_layer_stash_bytes": (_sz, [_cfgp]),
     "ptdp_stash_offset": (_sz, [_cfgp, _i]),
     "ptdp_workspace_bytes": (_sz, [_cfgp]),
+    "ptdp_workspace_offset": (_sz, [_cfgp, _i]),
     "ptdp_layer_flops_fwd": (_i64, [_cfgp]),
     "ptdp_batch_time": (C.c_double, [_i64, _i64, _i, C.c_double, C.c_double]),
     "ptdp_hash": (_u64, [_u64, _u32, _u32, _u64, _u64]),
@@ -108,6 +110,7 @@ SIGNATURES = {
     "ptdp_dropout_mask": (_i, [_vp, _i64, _f, _u64, _u32, _u32, _u64, _vp]),
     "ptdp_gemm": (_i, [_i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "ptdp_gemm_workspace_bytes": (_sz, []),
+    "ptdp_gemm_plan": (_i, [_i, _i, _i, _i, _i, _i, _sz, C.POINTER(_i), C.POINTER(_i), C.POINTER(_i)]),
     "ptdp_attn_fwd": (_i, [_i, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "ptdp_attn_bwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "ptdp_attn_masked_fwd": (_i, [_i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
@@ -215,6 +218,10 @@ def schedule_build(p, v, m, rank):
 
 def stash_offsets(cfg):
     return {name: lib.ptdp_stash_offset(C.byref(cfg), i) for i, name in enumerate(STASH_FIELDS)}
+
+
+def workspace_offsets(cfg):
+    return {name: lib.ptdp_workspace_offset(C.byref(cfg), i) for i, name in enumerate(WS_FIELDS)}
 
 
 def prof_collect():

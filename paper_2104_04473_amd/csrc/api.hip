@@ -75,6 +75,13 @@ static int validate(const ptdp_layer_cfg* c) {
   // LayerNorm keeps a row in registers: at most 8 vectors x 512 threads
   const int64_t per_vec = c->dtype == PTDP_BF16 ? 8 : 4;
   if (c->h > 8 * 512 * per_vec) return PTDP_E_UNSUPPORTED;
+  if (c->dtype == PTDP_BF16) {
+    // the bf16 GEMM addresses each operand through a 31-bit byte offset: refuse up front what a GEMM
+    // in the middle of a layer would refuse (the largest operands are w_1 / w_2 and the [T, 4h/t] activations)
+    const int64_t lim = 0x7fffffffll, T = (int64_t)c->s * c->b, fp = 4ll * c->h / c->t, qp = 3ll * c->h / c->t;
+    const int64_t wide = fp > qp ? fp : qp, big = wide > c->h ? wide : c->h;
+    if (2 * (int64_t)c->h * wide >= lim || 2 * T * big >= lim) return PTDP_E_UNSUPPORTED;
+  }
   return PTDP_OK;
 }
 
@@ -200,6 +207,14 @@ size_t ptdp_stash_offset(const ptdp_layer_cfg* cfg, int field) {
 size_t ptdp_workspace_bytes(const ptdp_layer_cfg* cfg) {
   if (validate(cfg) != PTDP_OK) return 0;
   return ws_layout(cfg).total;
+}
+
+size_t ptdp_workspace_offset(const ptdp_layer_cfg* cfg, int field) {
+  static_assert(PTDP_WS_DO == WS_H1 && PTDP_WS_DU == WS_H2 && PTDP_WS_DX1 == WS_X1 && PTDP_WS_CHAIN == WS_CHAIN &&
+                    PTDP_WS_DZ == WS_BIG && PTDP_WS_DCTX == WS_CTX && PTDP_WS_DQKV == WS_QKV,
+                "public workspace fields are the first internal ones, in order");
+  if (validate(cfg) != PTDP_OK || field < 0 || field >= PTDP_WS_NFIELDS) return (size_t)-1;
+  return ws_layout(cfg).off[field];
 }
 
 int64_t ptdp_layer_flops_fwd(const ptdp_layer_cfg* cfg) {
@@ -776,6 +791,18 @@ int ptdp_bias_dropout_add_bwd(int dtype, const void* dout, void* din, float* dbi
 size_t ptdp_colsum_scratch_bytes(int rows, int width) { return colsum_scratch_bytes(rows, width); }
 
 size_t ptdp_gemm_workspace_bytes(void) { return gemm_workspace_bytes(); }
+
+int ptdp_gemm_plan(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t workspace_bytes,
+                   int* dp_columns, int* sk_tiles, int* sk_workgroups) {
+  if (!dp_columns || !sk_tiles || !sk_workgroups) return PTDP_E_NULL_PTR;
+  if (M <= 0 || N <= 0 || K <= 0 || M % 8 || N % 8 || K % 8) return PTDP_E_INVALID_ARG;
+  const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+  const int cols = gemm_split_columns(M, N, K, out_f32, accumulate, has_bias, workspace_bytes);
+  *dp_columns = cols < tiles_n ? cols * 256 : N;
+  *sk_tiles = cols < tiles_n ? tiles_m * (tiles_n - cols) : 0;
+  *sk_workgroups = (int)(gemm_workspace_bytes() / (2 * 256 * 256 * sizeof(float)));
+  return PTDP_OK;
+}
 
 int ptdp_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t seed, uint32_t layer, uint32_t site,
                       uint64_t microbatch, void* stream) {

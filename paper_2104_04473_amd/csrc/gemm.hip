@@ -507,6 +507,29 @@ static int compute_units() {
 
 size_t gemm_workspace_bytes() { return (size_t)compute_units() * 2 * kSlabFloats * sizeof(float); }
 
+// How many of the 256-column tiles of C go to the one-workgroup-per-tile launch; the rest (fewer tiles
+// than compute units, so that one workgroup's k-range never reaches into a third tile) is split along k.
+// Splitting the last round along k saves the idle share of that round and costs two more launches plus
+// a round trip of the partial tiles through memory.  Fitted to measurements: about 1.8 us per k-step,
+// 15 us fixed + 0.23 us per remainder tile; with C accumulated in fp32 the extra pass over C makes it pay
+// only for long k.
+int gemm_split_columns(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t ws_bytes) {
+  const int ncu = compute_units();
+  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN, nk = (K + BK - 1) / BK;
+  const long long tiles = (long long)tiles_m * tiles_n;
+  const int rem = (int)(tiles % ncu);
+  const bool sk_out_ok = (out_f32 && accumulate && !has_bias) || !out_f32;
+  const double sk_saved_us = (1.0 - (double)rem / ncu) * nk * 1.8;
+  const double sk_cost_us = 15.0 + rem * (out_f32 ? 0.6 : 0.23);
+  if (!(ws_bytes >= gemm_workspace_bytes() && sk_out_ok && rem != 0 && sk_saved_us > sk_cost_us && (!out_f32 || nk >= 64)))
+    return tiles_n;
+  // whole columns only: the full rounds' tiles, rounded up to a column boundary, so that fewer than
+  // ncu tiles remain (rounding down would leave up to tiles_m - 1 more)
+  const long long full = (tiles / ncu) * ncu;
+  const int dp_cols = (int)((full + tiles_m - 1) / tiles_m);
+  return dp_cols < tiles_n ? dp_cols : tiles_n;
+}
+
 // Splits the columns into a part whose tiles fill whole rounds of the machine (one workgroup per tile)
 // and a remainder of less than one round that is spread evenly over all compute units in stream-K form.
 template <bool TA, bool TB>
@@ -525,21 +548,9 @@ static int launch_bf16_mode(const void* A, const void* B, void* C, const void* b
   g.ldb = TB ? (size_t)N : (size_t)K;
   g.ldc = (size_t)N;
 
+  const int dp_cols = gemm_split_columns(M, N, K, out_f32, accumulate, bias != nullptr, ws != nullptr ? ws_bytes : 0);
   const int ncu = compute_units();
-  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN, nk = (K + BK - 1) / BK;
-  const long long tiles = (long long)tiles_m * tiles_n;
-  const int rem = (int)(tiles % ncu);
-  const bool sk_out_ok = (out_f32 && accumulate && !bias) || !out_f32;
-  int dp_cols = tiles_n;
-  // Splitting the last round along k saves the idle share of that round and costs two more launches plus
-  // a round trip of the partial tiles through memory.  Fitted to measurements: about 1.8 us per k-step,
-  // 15 us fixed + 0.23 us per remainder tile; with C accumulated in fp32 the extra pass over C makes it pay
-  // only for long k.
-  const double sk_saved_us = (1.0 - (double)rem / ncu) * nk * 1.8;
-  const double sk_cost_us = 15.0 + rem * (out_f32 ? 0.6 : 0.23);
-  if (ws != nullptr && ws_bytes >= gemm_workspace_bytes() && sk_out_ok && rem != 0 && sk_saved_us > sk_cost_us &&
-      (!out_f32 || nk >= 64))
-    dp_cols = (int)((tiles / ncu) * ncu / tiles_m);   // the rest is fewer than ncu tiles
+  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
   const int n_dp = dp_cols < tiles_n ? dp_cols * kBN : N;
   if (n_dp > 0) {
     GemmArgs d = g;
@@ -554,9 +565,10 @@ static int launch_bf16_mode(const void* A, const void* B, void* C, const void* b
     GemmArgs r = g;
     r.N = N - n_dp;
     r.B = TB ? g.B + n_dp : g.B + (size_t)n_dp * K;
+    const int sk_tiles = tiles_m * ((r.N + kBN - 1) / kBN);
+    if (sk_tiles > ncu) return PTDP_E_STATE;   // a workgroup's range would span more than two tiles
     const int rc = launch_sk<TA, TB>(r, (float*)ws, ncu, st);
     if (rc != PTDP_OK) return rc;
-    const int sk_tiles = tiles_m * ((r.N + kBN - 1) / kBN);
     if (out_f32)
       hipLaunchKernelGGL(gemm_sk_reduce_kernel<true>, dim3(sk_tiles * 16), dim3(256), 0, st, (const float*)ws,
                          (void*)((float*)C + n_dp), (const bf16_t*)nullptr, M, r.N, K, (size_t)N, ncu);

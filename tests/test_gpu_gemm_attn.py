@@ -38,7 +38,8 @@ def test_gemm(dtype, mode, M, N, K):
 
 
 @pytest.mark.parametrize("mode", [B.GEMM_NN, B.GEMM_NT, B.GEMM_TN])
-@pytest.mark.parametrize("M,N,K", [(520, 776, 4168), (264, 4104, 4096), (2048, 1288, 4160), (2048, 10248, 4096)])
+@pytest.mark.parametrize("M,N,K", [(520, 776, 4168), (264, 4104, 4096), (2048, 1288, 4160), (2048, 10248, 4096),
+                                   (14336, 1792, 4096)])   # 56 row tiles: do not divide the compute-unit count
 def test_gemm_split_along_k(mode, M, N, K):
     """Tile counts that do not fill the compute units: the remaining tiles are split along k through the
     workspace and reduced in a fixed order (bf16 output, or += into the fp32 accumulator)."""
@@ -101,7 +102,7 @@ def test_attention_forward_backward(dtype, s, b, heads, dh):
     cfg = L.LayerConfig(h=hp, a=heads, t=1, s=s, b=b)
     wctx, probs, wlse = L.attention_core(np64(qkv), cfg)
     assert_close(np64(ctx), wctx, dtype, "ctx")
-    assert_close(np64(lse), wlse, B.F32, "lse", 30 if dtype == B.BF16 else 1)
+    assert_close(np64(lse), wlse, B.F32, "lse")
     dctx = randn((s, b, hp), dtype, 7)
     dqkv = torch.zeros_like(qkv)
     delta = torch.zeros((b, heads, s), device="cuda")

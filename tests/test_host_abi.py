@@ -159,3 +159,53 @@ def test_batch_time_matches_oracle_and_rejects_bad_input():
     for bad in [(0, 1, 1, 1.0, 1.0), (8, 3, 2, 1.0, 1.0), (8, 2, 0, 1.0, 1.0), (8, 2, 2, -1.0, 1.0),
                 (8, 2, 2, float("nan"), 1.0), (8, 2, 2, 1.0, float("inf"))]:
         assert math.isnan(B.ptdp_batch_time(*bad))
+
+
+def _plan(M, N, K, out_f32=0, accumulate=0, has_bias=0, ws=None):
+    ws = B.ptdp_gemm_workspace_bytes() if ws is None else ws
+    d, t, g = C.c_int(0), C.c_int(0), C.c_int(0)
+    assert B.ptdp_gemm_plan(M, N, K, out_f32, accumulate, has_bias, ws, C.byref(d), C.byref(t), C.byref(g)) == B.OK
+    return d.value, t.value, g.value
+
+
+def test_gemm_k_split_covers_every_k_step_once():
+    """The remainder tiles of a GEMM are cut into equal contiguous (tile, k-step) ranges, one per workgroup,
+    and a workgroup handles at most two tiles: replay that arithmetic on the host for shapes whose row-tile
+    count does not divide the number of compute units, and count how often each k-step is taken."""
+    shapes = [(14336, 12800, 51200), (26624, 11264, 33792), (2048, 9600, 25600), (2048, 25600, 12800),
+              (2048, 4608, 12288), (8192, 6144, 2048), (14336, 12800, 4096), (7 * 256, 37 * 256, 8192),
+              (56 * 256, 5 * 256, 16384), (3 * 256, 87 * 256, 6400), (8, 264 * 256, 4096), (2048 + 8, 9600 + 8, 25600 + 8)]
+    n_split = 0
+    for (M, N, K) in shapes:
+        for out_f32, acc in ((0, 0), (1, 1)):
+            dp_cols, sk_tiles, nblk = _plan(M, N, K, out_f32, acc)
+            tiles_m, tiles_n, nk = -(-M // 256), -(-N // 256), -(-K // 64)
+            assert dp_cols == N or dp_cols % 256 == 0
+            if sk_tiles == 0:
+                assert dp_cols == N
+                continue
+            n_split += 1
+            assert sk_tiles < nblk, (M, N, K, sk_tiles)
+            assert sk_tiles == tiles_m * (tiles_n - dp_cols // 256)
+            total = sk_tiles * nk
+            seen = np.zeros(total, dtype=np.int32)
+            for blk in range(nblk):
+                it, end = total * blk // nblk, total * (blk + 1) // nblk
+                for seg in range(2):                      # the kernel's loop: at most two partial tiles
+                    if it >= end:
+                        break
+                    kt0 = it % nk
+                    kt1 = min(nk, kt0 + (end - it))
+                    seen[it:it + kt1 - kt0] += 1
+                    it += kt1 - kt0
+                assert it == end, (M, N, K, blk)
+            assert (seen == 1).all(), (M, N, K)
+    assert n_split >= 6
+    assert _plan(14336, 12800, 51200, ws=0) == (12800, 0, 256)        # no workspace: never split
+
+
+def test_cfg_refuses_operands_beyond_the_gemm_offset_range():
+    big = B.make_cfg(h=25600, a=160, t=1, s=2048, b=1, dtype=B.BF16)    # w_1 is 5.2 GB
+    assert B.ptdp_cfg_validate(C.byref(big)) == B.E_UNSUPPORTED
+    assert B.ptdp_layer_stash_bytes(C.byref(big)) == 0
+    assert B.ptdp_cfg_validate(C.byref(B.make_cfg(h=25600, a=160, t=8, s=2048, b=1, dtype=B.BF16))) == B.OK
