@@ -38,24 +38,35 @@ def run_chunk_against_oracle(cfg, n_layers, say, first_layer=0, mb=0):
     Ps = [params_np(P) for P in rig.params]
     del rig
     torch.cuda.empty_cache()
-    errs = {}
+    errs, failed = {}, []
+
+    def close(key, got, want, what):
+        try:
+            errs[key] = assert_close(got, want, cfg.dtype, what)
+        except AssertionError as e:                                           # keep going: report every tensor at the end
+            failed.append(str(e).splitlines()[0])
+
     t0 = time.time()
     cur = np64(x)
     caches = []
     for l in range(n_layers):
-        errs["x%d" % l] = assert_close(got_in[l], cur, cfg.dtype, "input of layer %d" % l)
+        close("x%d" % l, got_in[l], cur, "input of layer %d" % l)
         cur, c = L.layer_forward(cur, Ps[l], ocfg, first_layer + l, mb)
         caches.append(c)
         say("oracle forward layer %d done (%.0f s)" % (l, time.time() - t0))
-    errs["y"] = assert_close(got_y, cur, cfg.dtype, "y")
+    close("y", got_y, cur, "y")
     d = np64(dy)
     for l in reversed(range(n_layers)):
         d, g = L.layer_backward(d, Ps[l], ocfg, caches[l])
         caches[l] = None                                                      # frees that layer's probabilities
         for k in B.PARAM_NAMES:
-            errs["%s[%d]" % (k, l)] = assert_close(got_grads[l][k], g[k], cfg.dtype, "grad %s of layer %d" % (k, l))
+            close("%s[%d]" % (k, l), got_grads[l][k], g[k], "grad %s of layer %d" % (k, l))
         say("oracle backward layer %d done (%.0f s)" % (l, time.time() - t0))
-    errs["dx"] = assert_close(got_dx, d, cfg.dtype, "dx")
+    close("dx", got_dx, d, "dx")
+    for msg in failed:
+        say("FAILED " + msg)
+    say("errors: " + " ".join("%s=%.1e" % kv for kv in errs.items()))
+    assert not failed, failed
     say("largest relative L2 error %.3e (%s)" % (max(errs.values()), max(errs, key=errs.get)))
     return errs
 
@@ -156,9 +167,9 @@ def test_interleaved_share_at_gpt3_shape(recompute, say):
     else:
         activations = peak * n_layers * layer_stash
     want = weights + gradients + io_bytes + chunks[0].workspace_bytes() + activations
-    # torch rounds every allocation up to its 512-byte granule (2 MiB for large blocks)
-    n_allocs = v * n_layers * 24 + 4 * v * m + 3
-    assert want <= resident <= want + n_allocs * (2 << 20), (resident, want)
+    # torch's allocator hands out blocks a little larger than asked for (512-byte granules, unsplit remainders
+    # below 1 MiB): allow 0.1 %
+    assert want <= resident <= want * 1.001, (resident, want)
     assert before_pool - base >= weights + gradients + io_bytes
     say("resident %.2f GiB = weights %.2f + fp32 grads %.2f + stage io %.2f + workspace %.2f + activations %.2f GiB "
         "(%d pairs in flight)" % (resident / 2 ** 30, weights / 2 ** 30, gradients / 2 ** 30, io_bytes / 2 ** 30,

@@ -292,8 +292,7 @@ def test_head_step_sampled_parity_at_full_size():
         du = (p / T) @ E
         wdy, _, _ = L.layernorm_backward(du[None, :], yv[t:t + 1], np.ones(h), mu, rstd)
         want_rows.append(wdy[0])
-        assert_close(got_dy[t], wdy[0], B.BF16, "dy row %d" % t)
-    assert_close(got_dy[sample], np.array(want_rows), B.BF16, "sampled dy rows")
+    assert_close(got_dy[sample], np.array(want_rows), B.BF16, "sampled dy rows")   # incl. the bound on every single row
     assert abs(loss.item() - np64(tl).mean()) <= 1e-5 * abs(loss.item())
     assert np.isfinite(np64(dw)).all() and np.abs(np64(dw)).max() > 0
 
