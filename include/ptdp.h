@@ -365,6 +365,21 @@ int ptdp_bias_dropout_add_bwd(int dtype, const void* dout, void* din, float* dbi
                               int width, float p, uint64_t seed, uint32_t layer, uint32_t site,
                               uint64_t microbatch, void* stream);
 size_t ptdp_colsum_scratch_bytes(int rows, int width);
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): ptdp_bias_dropout_add_bwd
+ * without the scratch argument.  The column-sum partials live in a static device
+ * array of ptdp_noalloc_scratch_bytes() (8 MiB) that each GPU the library runs on
+ * holds until the process ends; the call allocates and frees nothing.  Same
+ * kernels, same results, bit for bit.  PTDP_E_TOO_SMALL when
+ * ptdp_colsum_scratch_bytes(rows, width) exceeds the array (nothing is launched),
+ * PTDP_E_STATE while profiling is on (profiling creates events).  Every call on a
+ * GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race; calls in stream order do not, and nothing needs clearing between
+ * them. */
+int ptdp_bias_dropout_add_bwd_noalloc(int dtype, const void* dout, void* din, float* dbias, int rows, int width,
+                                      float p, uint64_t seed, uint32_t layer, uint32_t site, uint64_t microbatch,
+                                      void* stream);
+size_t ptdp_noalloc_scratch_bytes(void);
 /* keep[i] = 1/0 for i < n: the dropout keep-mask as bytes (test hook). */
 int ptdp_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t seed, uint32_t layer, uint32_t site,
                       uint64_t microbatch, void* stream);

@@ -28,6 +28,8 @@ static bool get_event(hipEvent_t* e) {
   return hipEventCreate(e) == hipSuccess;
 }
 
+bool profiling_enabled() { return g_prof_on; }
+
 Launch::Launch(int family, double work, hipStream_t stream) : stream_(stream), slot_(-1), status_(PTDP_OK), closed_(false) {
   (void)hipGetLastError();  // do not inherit a stale error
   if (!g_prof_on) return;
@@ -787,6 +789,19 @@ int ptdp_bias_dropout_add_bwd(int dtype, const void* dout, void* din, float* dbi
   return launch_bda_bwd(dtype, dout, din, dbias, scratch, rows, width, p, dropout_key(seed, layer, site, microbatch),
                         (hipStream_t)stream);
 }
+
+int ptdp_bias_dropout_add_bwd_noalloc(int dtype, const void* dout, void* din, float* dbias, int rows, int width,
+                                      float p, uint64_t seed, uint32_t layer, uint32_t site, uint64_t microbatch,
+                                      void* stream) {
+  PTDP_TRY(check_rw(dtype, rows, width));
+  if (!(p >= 0.f && p < 1.f) || site > 1 || dout == din) return PTDP_E_INVALID_ARG;
+  if (!dout || !din || !dbias) return PTDP_E_NULL_PTR;
+  if (profiling_enabled()) return PTDP_E_STATE;   // profiling creates events: not for callers that may not allocate
+  return launch_bda_bwd_static(dtype, dout, din, dbias, rows, width, p, dropout_key(seed, layer, site, microbatch),
+                               (hipStream_t)stream);
+}
+
+size_t ptdp_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
 
 size_t ptdp_colsum_scratch_bytes(int rows, int width) { return colsum_scratch_bytes(rows, width); }
 

@@ -140,6 +140,11 @@ int launch_bda_fwd(int dtype, const void* in, const void* bias, const void* resi
                    int width, float p, uint64_t key, hipStream_t st);
 int launch_bda_bwd(int dtype, const void* dout, void* din, float* dbias, void* scratch, int rows, int width,
                    float p, uint64_t key, hipStream_t st);
+// same, with the column-sum partials in a static device array of kStaticScratchBytes (allocates nothing)
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+int launch_bda_bwd_static(int dtype, const void* dout, void* din, float* dbias, int rows, int width, float p,
+                          uint64_t key, hipStream_t st);
+bool profiling_enabled();
 int launch_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t key, hipStream_t st);
 size_t colsum_scratch_bytes(int rows, int width);
 // out[width] (fp32) += column sums of in[rows, width]

@@ -570,6 +570,36 @@ int launch_bda_bwd(int dtype, const void* dout, void* din, float* dbias, void* s
                             : bda_bwd_t<float>(dout, din, dbias, scratch, rows, width, p, key, st);
 }
 
+// Column-sum partials for callers that may not allocate: one array per device, kept until the process
+// ends.  In host code `scratch` is only a handle for hipGetSymbolAddress, never a device address: every
+// launch below is handed the address looked up once per device, with that device current.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+static int static_scratch(void** out) {
+  const int d = device_slot();
+  if (d < 0) return PTDP_E_HIP;
+  if (!g_scratch_ptr[d]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return PTDP_E_HIP;
+    g_scratch_ptr[d] = ptr;
+  }
+  *out = g_scratch_ptr[d];
+  return PTDP_OK;
+}
+
+// launch_bda_bwd with the partials in this device's static array (every partial that the finish kernel reads
+// is written by the first kernel of the same call, so nothing has to be cleared between calls)
+int launch_bda_bwd_static(int dtype, const void* dout, void* din, float* dbias, int rows, int width, float p,
+                          uint64_t key, hipStream_t st) {
+  if (colsum_scratch_bytes(rows, width) > kStaticScratchBytes) return PTDP_E_TOO_SMALL;
+  if (rows == 0) return PTDP_OK;
+  void* ptr = nullptr;
+  const int rc = static_scratch(&ptr);
+  if (rc != PTDP_OK) return rc;
+  return launch_bda_bwd(dtype, dout, din, dbias, ptr, rows, width, p, key, st);
+}
+
 template <typename T>
 static int colsum_t(const void* in, float* out, void* scratch, int rows, int width, hipStream_t st) {
   constexpr int N = Vec16<T>::N;
