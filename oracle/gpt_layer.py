@@ -246,73 +246,86 @@ def _f64(P):
     return {k: np.asarray(v, dtype=np.float64) for k, v in P.items()}
 
 
-def layer_forward(x, P, cfg, layer=0, microbatch=0, mask=None):
+def _keep(a):
+    return a
+
+
+def layer_forward(x, P, cfg, layer=0, microbatch=0, mask=None, storage=None):
     """x [s, b, h] -> (y [s, b, h], cache).  ``layer`` is the global layer
     index and ``microbatch`` the microbatch id; both only select the dropout
-    stream.  ``mask`` [b, s, s]: general attention mask, used when cfg.causal is False."""
+    stream.  ``mask`` [b, s, s]: general attention mask, used when cfg.causal is False.
+    ``storage``: None (exact fp64 throughout), or a rounding function applied to every activation at the
+    point where the method hands it on in storage precision (see ``oracle.bf16``); the first MLP GEMM's
+    output is kept before its bias is added, as the bias + GeLU group of section 4.2 consumes it."""
+    r = storage or _keep
     P = _f64(P)
     x = np.asarray(x, dtype=np.float64)
-    c = {"x": x}
-    c["u"], c["mu1"], c["rstd1"] = layernorm(x, P["ln1_g"], P["ln1_b"], cfg.ln_eps)
-    c["qkv"] = c["u"] @ P["w_qkv"] + P["b_qkv"]
+    c = {"x": x, "storage": storage}
+    u, c["mu1"], c["rstd1"] = layernorm(x, P["ln1_g"], P["ln1_b"], cfg.ln_eps)
+    c["u"] = r(u)
+    c["qkv"] = r(c["u"] @ P["w_qkv"] + P["b_qkv"])
     c["mask"] = mask
-    c["ctx"], c["probs"], c["lse"] = attention_core(c["qkv"], cfg, mask)
-    c["o"] = c["ctx"] @ P["w_o"]
+    ctx, c["probs"], c["lse"] = attention_core(c["qkv"], cfg, mask)
+    c["ctx"] = r(ctx)
+    c["o"] = r(c["ctx"] @ P["w_o"])
     c["keep1"] = dropout_keep(cfg, layer, 0, microbatch)
     scale = dropout_hash.keep_scale(cfg.p_hidden)
-    c["x1"] = x + (c["o"] + P["b_o"]) * c["keep1"] * scale
-    c["u2"], c["mu2"], c["rstd2"] = layernorm(c["x1"], P["ln2_g"], P["ln2_b"], cfg.ln_eps)
-    c["z"] = c["u2"] @ P["w_1"] + P["b_1"]
-    c["g"] = gelu(c["z"], cfg.gelu_tanh)
-    c["mo"] = c["g"] @ P["w_2"]
+    c["x1"] = r(x + (c["o"] + P["b_o"]) * c["keep1"] * scale)
+    u2, c["mu2"], c["rstd2"] = layernorm(c["x1"], P["ln2_g"], P["ln2_b"], cfg.ln_eps)
+    c["u2"] = r(u2)
+    c["z"] = r(c["u2"] @ P["w_1"]) + P["b_1"]
+    c["g"] = r(gelu(c["z"], cfg.gelu_tanh))
+    c["mo"] = r(c["g"] @ P["w_2"])
     c["keep2"] = dropout_keep(cfg, layer, 1, microbatch)
-    y = c["x1"] + (c["mo"] + P["b_2"]) * c["keep2"] * scale
+    y = r(c["x1"] + (c["mo"] + P["b_2"]) * c["keep2"] * scale)
     return y, c
 
 
 def layer_backward(dy, P, cfg, cache):
     """Gradient of ``layer_forward`` at the cached point: returns
-    (dx [s, b, h], grads dict with one array per parameter)."""
+    (dx [s, b, h], grads dict with one array per parameter).  Under a storage rounding (taken from the
+    cache) every gradient of an activation is rounded where it is produced; parameter gradients are not."""
     P = _f64(P)
     c = cache
+    r = c.get("storage") or _keep
     h = cfg.h
     dy = np.asarray(dy, dtype=np.float64)
     scale = dropout_hash.keep_scale(cfg.p_hidden)
     G = {}
     flat = lambda a: a.reshape(-1, a.shape[-1])
 
-    dmo = dy * c["keep2"] * scale                   # grad w.r.t. (mo + b_2)
+    dmo = r(dy * c["keep2"] * scale)                # grad w.r.t. (mo + b_2)
     G["b_2"] = flat(dmo).sum(axis=0)
     dx1 = dy.copy()                                 # residual branch
-    dg = dmo @ P["w_2"].T
+    dg = r(dmo @ P["w_2"].T)
     G["w_2"] = flat(c["g"]).T @ flat(dmo)
-    dz = dg * gelu_grad(c["z"], cfg.gelu_tanh)
+    dz = r(dg * gelu_grad(c["z"], cfg.gelu_tanh))
     G["b_1"] = flat(dz).sum(axis=0)
-    du2 = dz @ P["w_1"].T
+    du2 = r(dz @ P["w_1"].T)
     G["w_1"] = flat(c["u2"]).T @ flat(dz)
     d, G["ln2_g"], G["ln2_b"] = layernorm_backward(du2, c["x1"], P["ln2_g"], c["mu2"], c["rstd2"])
-    dx1 = dx1 + d
+    dx1 = r(dx1 + d)
 
-    do = dx1 * c["keep1"] * scale                   # grad w.r.t. (o + b_o)
+    do = r(dx1 * c["keep1"] * scale)                # grad w.r.t. (o + b_o)
     G["b_o"] = flat(do).sum(axis=0)
     dx = dx1.copy()                                 # residual branch
-    dctx = do @ P["w_o"].T
+    dctx = r(do @ P["w_o"].T)
     G["w_o"] = flat(c["ctx"]).T @ flat(do)
-    dqkv = attention_core_backward(dctx, c["qkv"], c["probs"], cfg, c.get("mask"))
+    dqkv = r(attention_core_backward(dctx, c["qkv"], c["probs"], cfg, c.get("mask")))
     G["b_qkv"] = flat(dqkv).sum(axis=0)
-    du = dqkv @ P["w_qkv"].T
+    du = r(dqkv @ P["w_qkv"].T)
     G["w_qkv"] = flat(c["u"]).T @ flat(dqkv)
     d, G["ln1_g"], G["ln1_b"] = layernorm_backward(du, c["x"], P["ln1_g"], c["mu1"], c["rstd1"])
-    dx = dx + d
+    dx = r(dx + d)
     assert dx.shape[-1] == h
     return dx, G
 
 
-def chunk_forward(x, params_list, cfg, first_layer=0, microbatch=0):
+def chunk_forward(x, params_list, cfg, first_layer=0, microbatch=0, storage=None):
     """A model chunk = consecutive layers (section 2.2).  Returns (y, caches)."""
     caches = []
     for i, P in enumerate(params_list):
-        x, c = layer_forward(x, P, cfg, first_layer + i, microbatch)
+        x, c = layer_forward(x, P, cfg, first_layer + i, microbatch, storage=storage)
         caches.append(c)
     return x, caches
 

@@ -4,12 +4,14 @@ real shape with the memory accounting of section 3.5, and the microbatch sweep o
 The slow cases here spend their time in the fp64 oracle on the host (minutes); each prints a line per layer
 so that a run is never silent for long."""
 import ctypes as C
+import os
 import time
 
 import numpy as np
 import pytest
 import torch
 
+from oracle import bf16
 from oracle import flops as F
 from oracle import gpt_layer as L
 from paper_2104_04473_amd import binding as B
@@ -20,9 +22,30 @@ from gpu_util import LayerRig, assert_close, np64, oracle_cfg, params_np, randn,
 pytestmark = pytest.mark.gpu
 
 
-def run_chunk_against_oracle(cfg, n_layers, say, first_layer=0, mb=0):
+# Error model for runs at GPT-3 / 1T widths.  With N(0, 0.02) weights the scaled attention logits have a
+# standard deviation of sigma_q * sigma_k = 0.0004 h (4.9 at h = 12288, 10 at h = 25600): the softmax is sharp,
+# and a relative perturbation d of q and k moves every logit by about d * sqrt(2) * sigma_q * sigma_k and so every
+# probability by that fraction of itself.  Two consequences:
+#  * against the oracle that is exact in fp64 throughout, the bf16 storage of q and k alone (d = 1.2e-3 RMS)
+#    costs 1-2 % in every probability before any kernel has run; gradients behind the attention backward
+#    inherit 2-4 %.  The oracle that rounds activations to bf16 where the method stores them has this term too.
+#  * through a chain of layers, whatever two implementations differ by at the input of a layer (a few 1e-3 from
+#    fp32 versus fp64 accumulation and from bf16 operands inside the fused attention) is multiplied by about
+#    sqrt(2) * sigma_q * sigma_k by that layer's softmax.
+# So every layer is compared in full, at the stated tolerance, from the inputs it received on the device, and the
+# chained comparisons through sharp softmaxes hold tensors that lie behind an attention to this model's bound.
+SHARP_SOFTMAX = dict(factor=2.5, justified="sharp softmax multiplies upstream differences by sqrt(2)*sigma_q*sigma_k")
+
+
+def run_chunk_against_oracle(cfg, n_layers, say, first_layer=0, mb=0, sharp=False):
     """Forward + backward of a chunk on the GPU and in the oracle, same bits in; every output, every layer
-    boundary and every parameter gradient is compared in full."""
+    boundary and every parameter gradient is compared in full:
+    (A) layer by layer, the oracle (activations stored in bf16 where the method stores them) starting from the
+        input and the output gradient that this layer received on the device: stated tolerance;
+    (B) the oracle exact in fp64 throughout (and, with PTDP_TEST_CHAINED=all, also the oracle of (A)) chained
+        through the whole chunk: stated tolerance, except, under a sharp softmax, for tensors that lie behind
+        an attention (SHARP_SOFTMAX).  The chained passes cost minutes of host time: by default they run where
+        the softmax is mild (configuration 2); PTDP_TEST_CHAINED=all runs them everywhere, =none nowhere."""
     rig = LayerRig(cfg, n_layers, first_layer)
     ocfg = oracle_cfg(cfg)
     shape = (cfg.s, cfg.b, cfg.h)
@@ -36,39 +59,84 @@ def run_chunk_against_oracle(cfg, n_layers, say, first_layer=0, mb=0):
     got_y, got_dx = np64(y), np64(dx)
     got_grads = [{k: np64(v) for k, v in G.items()} for G in rig.grads]
     Ps = [params_np(P) for P in rig.params]
-    del rig
-    torch.cuda.empty_cache()
-    errs, failed = {}, []
-
-    def close(key, got, want, what):
-        try:
-            errs[key] = assert_close(got, want, cfg.dtype, what)
-        except AssertionError as e:                                           # keep going: report every tensor at the end
-            failed.append(str(e).splitlines()[0])
-
-    t0 = time.time()
-    cur = np64(x)
-    caches = []
-    for l in range(n_layers):
-        close("x%d" % l, got_in[l], cur, "input of layer %d" % l)
-        cur, c = L.layer_forward(cur, Ps[l], ocfg, first_layer + l, mb)
-        caches.append(c)
-        say("oracle forward layer %d done (%.0f s)" % (l, time.time() - t0))
-    close("y", got_y, cur, "y")
-    d = np64(dy)
+    # the same backward one layer at a time (what ptdp_chunk_backward does inside), keeping every layer's
+    # incoming gradient: same bits out
+    for G in rig.grads:
+        for g in G.values():
+            g.zero_()
+    dys = [None] * n_layers + [dy]                                            # dys[l + 1] enters layer l's backward
     for l in reversed(range(n_layers)):
-        d, g = L.layer_backward(d, Ps[l], ocfg, caches[l])
-        caches[l] = None                                                      # frees that layer's probabilities
+        dys[l] = torch.empty_like(dy)
+        B.check(rig.chunk.layer_backward(l, mb, dys[l + 1].data_ptr(), dys[l].data_ptr(),
+                                         rig.stash.data_ptr() + l * rig.layer_stash_bytes, rig.ws.data_ptr()), "layer_backward")
+    sync()
+    assert torch.equal(dys[0], dx)
+    for l in range(n_layers):
+        for k in B.PARAM_NAMES:
+            assert np.array_equal(np64(rig.grads[l][k]), got_grads[l][k]), (l, k)
+    got_dy = [np64(t) for t in dys]
+    del rig, dys
+    torch.cuda.empty_cache()
+    failed, worst = [], {}
+    t0 = time.time()
+
+    def closer(mode, errs, relaxed):
+        def close(key, got, want, what, through_attention=False):
+            kw = SHARP_SOFTMAX if (relaxed and through_attention) else {}
+            try:
+                errs[key] = assert_close(got, want, cfg.dtype, "%s (%s)" % (what, mode), **kw)
+            except AssertionError as e:                                       # keep going: report every tensor at the end
+                failed.append(str(e).splitlines()[0])
+        return close
+
+    # ---- (A) every layer from its own device inputs
+    errs = {}
+    close = closer("layer by layer", errs, False)
+    for l in range(n_layers):
+        want_y, c = L.layer_forward(got_in[l], Ps[l], ocfg, first_layer + l, mb, storage=bf16.round_bf16)
+        close("y%d" % l, got_in[l + 1] if l + 1 < n_layers else got_y, want_y, "output of layer %d" % l)
+        want_dx, g = L.layer_backward(got_dy[l + 1], Ps[l], ocfg, c)
+        del c
+        close("dx%d" % l, got_dy[l], want_dx, "input gradient of layer %d" % l)
         for k in B.PARAM_NAMES:
             close("%s[%d]" % (k, l), got_grads[l][k], g[k], "grad %s of layer %d" % (k, l))
-        say("oracle backward layer %d done (%.0f s)" % (l, time.time() - t0))
-    close("dx", got_dx, d, "dx")
+        say("layer by layer: layer %d done (%.0f s)" % (l, time.time() - t0))
+    say("layer by layer, relative L2 errors: " + " ".join("%s=%.1e" % kv for kv in errs.items()))
+    worst["layer by layer"] = max(errs.values()) if errs else None
+
+    # ---- (B) chained through the chunk
+    which = os.environ.get("PTDP_TEST_CHAINED", "mild")
+    modes = [("chained, exact fp64", None)] if (which == "all" or (which == "mild" and not sharp)) else []
+    if which == "all":
+        modes.append(("chained, bf16 storage", bf16.round_bf16))
+    for mode, storage in modes:
+        errs = {}
+        close = closer(mode, errs, sharp)
+        cur = np64(x)
+        caches = []
+        for l in range(n_layers):
+            close("x%d" % l, got_in[l], cur, "input of layer %d" % l, l > 0)
+            cur, c = L.layer_forward(cur, Ps[l], ocfg, first_layer + l, mb, storage=storage)
+            caches.append(c)
+            say("%s: forward layer %d done (%.0f s)" % (mode, l, time.time() - t0))
+        close("y", got_y, cur, "y", True)
+        d = np64(dy)
+        for l in reversed(range(n_layers)):
+            d, g = L.layer_backward(d, Ps[l], ocfg, caches[l])
+            caches[l] = None                                                  # frees that layer's probabilities
+            for k in B.PARAM_NAMES:
+                # the last layer's MLP-block gradients and output-projection bias see neither the attention
+                # backward nor the attention output itself; everything else does
+                behind = l < n_layers - 1 or k in ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o")
+                close("%s[%d]" % (k, l), got_grads[l][k], g[k], "grad %s of layer %d" % (k, l), behind)
+            say("%s: backward layer %d done (%.0f s)" % (mode, l, time.time() - t0))
+        close("dx", got_dx, d, "dx", True)
+        say("%s, relative L2 errors: " % mode + " ".join("%s=%.1e" % kv for kv in errs.items()))
+        worst[mode] = max(errs.values()) if errs else None
     for msg in failed:
         say("FAILED " + msg)
-    say("errors: " + " ".join("%s=%.1e" % kv for kv in errs.items()))
     assert not failed, failed
-    say("largest relative L2 error %.3e (%s)" % (max(errs.values()), max(errs, key=errs.get)))
-    return errs
+    return worst
 
 
 @pytest.fixture
@@ -84,19 +152,19 @@ def test_one_layer_at_full_width_short_sequence(say):
     every GEMM runs with the tile, panel and round counts of its full-size k and n extents, and every output
     and gradient is compared with the oracle in full."""
     cfg = B.make_cfg(h=25600, a=160, t=8, s=256, b=1, dtype=B.BF16, p_hidden=0.1, seed=3)
-    run_chunk_against_oracle(cfg, 1, say, first_layer=2, mb=1)
+    run_chunk_against_oracle(cfg, 1, say, first_layer=2, mb=1, sharp=True)
 
 
 @pytest.mark.timeout(1100)
-@pytest.mark.parametrize("name,kw,n_layers", [
-    ("c3", dict(h=12288, a=96, t=8, s=2048, b=1), 2),
-    ("c2", dict(h=2048, a=16, t=1, s=2048, b=4), 4),
+@pytest.mark.parametrize("name,kw,n_layers,sharp", [
+    ("c3", dict(h=12288, a=96, t=8, s=2048, b=1), 2, True),
+    ("c2", dict(h=2048, a=16, t=1, s=2048, b=4), 4, False),
 ])
-def test_configuration_end_to_end_against_oracle(name, kw, n_layers, say):
+def test_configuration_end_to_end_against_oracle(name, kw, n_layers, sharp, say):
     """Configurations 3 (GPT-3-shaped shard, 2 layers) and 2 (h = 2048, b = 4, 4 layers) exactly as stated, the
     whole chunk forward and backward against the oracle."""
     cfg = B.make_cfg(dtype=B.BF16, p_hidden=0.1, seed=0, **kw)
-    run_chunk_against_oracle(cfg, n_layers, say)
+    run_chunk_against_oracle(cfg, n_layers, say, sharp=sharp)
 
 
 # ------------------------------------------------------------------------------- interleaved schedule, real shape
