@@ -392,23 +392,26 @@ int ptdp_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t seed, uint32_t
  * accumulated (+=) when accumulate != 0.  bias [N] in `dtype` or NULL.  bf16
  * needs M, N, K multiples of 8 and operands below 2 GiB.  workspace (dev, may
  * be NULL): ptdp_gemm_workspace_bytes() bytes of scratch; with it, a tile count
- * that does not fill the compute units evenly is finished by cutting the last,
- * incomplete round of tiles along k: partial tiles go to the workspace and are
- * summed in a fixed order, so results stay bit-reproducible. */
+ * that does not fill the compute units evenly is finished by giving each tile of
+ * the last, incomplete round to several workgroups that split its k range:
+ * partial tiles go to the workspace and are summed in a fixed order, so results
+ * stay bit-reproducible. */
 enum { PTDP_GEMM_NN = 0, PTDP_GEMM_NT = 1, PTDP_GEMM_TN = 2 };
 int ptdp_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N,
               int K, int out_f32, int accumulate, void* workspace, size_t workspace_bytes, void* stream);
 size_t ptdp_gemm_workspace_bytes(void);
-/* Host only (no device work): how ptdp_gemm splits a bf16 call (appendix: the
- * GEMMs of a layer).  *dp_columns = columns of C computed one workgroup per
- * 256 x 256 tile (a multiple of 256, or N); the remaining *sk_tiles tiles
- * (always fewer than *sk_workgroups) have their (tile, 64-wide k-step) space cut
- * into *sk_workgroups equal contiguous ranges, workgroup i taking
- * [total*i/n, total*(i+1)/n) with tiles numbered row tile fastest.
+/* Host only (no device work): how ptdp_gemm cuts a bf16 call (appendix: the
+ * GEMMs of a layer).  *dp_columns = columns of C computed in whole rounds, one
+ * workgroup per 256 x 256 tile (a multiple of 256, or N when nothing is split).
+ * The remaining tiles, numbered row tile fastest, form *n_groups (0..2)
+ * consecutive groups: group j has group_tiles[j] tiles and gives each of them to
+ * group_parts[j] workgroups, part p of which takes the 64-wide k-steps
+ * [nk*p/parts, nk*(p+1)/parts) of that tile; tiles x parts never exceeds the
+ * number of compute units.  group_tiles / group_parts: two ints each.
  * has_bias / workspace_bytes as in the call being planned.  Returns 0, or
  * PTDP_E_INVALID_ARG / PTDP_E_NULL_PTR. */
 int ptdp_gemm_plan(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t workspace_bytes,
-                   int* dp_columns, int* sk_tiles, int* sk_workgroups);
+                   int* dp_columns, int* n_groups, int* group_tiles, int* group_parts);
 
 /* Fused causal attention over qkv [s, b, 3hp] (scale 1/sqrt(dh), implicit
  * causal mask, softmax, times V; section 4.2's scale+mask+softmax fusion

@@ -112,7 +112,7 @@ SIGNATURES = {
     "ptdp_dropout_mask": (_i, [_vp, _i64, _f, _u64, _u32, _u32, _u64, _vp]),
     "ptdp_gemm": (_i, [_i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "ptdp_gemm_workspace_bytes": (_sz, []),
-    "ptdp_gemm_plan": (_i, [_i, _i, _i, _i, _i, _i, _sz, C.POINTER(_i), C.POINTER(_i), C.POINTER(_i)]),
+    "ptdp_gemm_plan": (_i, [_i, _i, _i, _i, _i, _i, _sz, C.POINTER(_i), C.POINTER(_i), C.POINTER(_i), C.POINTER(_i)]),
     "ptdp_attn_fwd": (_i, [_i, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "ptdp_attn_bwd": (_i, [_i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "ptdp_attn_masked_fwd": (_i, [_i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),

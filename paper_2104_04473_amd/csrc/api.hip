@@ -808,14 +808,12 @@ size_t ptdp_colsum_scratch_bytes(int rows, int width) { return colsum_scratch_by
 size_t ptdp_gemm_workspace_bytes(void) { return gemm_workspace_bytes(); }
 
 int ptdp_gemm_plan(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t workspace_bytes,
-                   int* dp_columns, int* sk_tiles, int* sk_workgroups) {
-  if (!dp_columns || !sk_tiles || !sk_workgroups) return PTDP_E_NULL_PTR;
+                   int* dp_columns, int* n_groups, int* group_tiles, int* group_parts) {
+  if (!dp_columns || !n_groups || !group_tiles || !group_parts) return PTDP_E_NULL_PTR;
   if (M <= 0 || N <= 0 || K <= 0 || M % 8 || N % 8 || K % 8) return PTDP_E_INVALID_ARG;
-  const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
-  const int cols = gemm_split_columns(M, N, K, out_f32, accumulate, has_bias, workspace_bytes);
-  *dp_columns = cols < tiles_n ? cols * 256 : N;
-  *sk_tiles = cols < tiles_n ? tiles_m * (tiles_n - cols) : 0;
-  *sk_workgroups = (int)(gemm_workspace_bytes() / (2 * 256 * 256 * sizeof(float)));
+  int cols = 0;
+  gemm_plan_query(M, N, K, out_f32, accumulate, has_bias, workspace_bytes, &cols, n_groups, group_tiles, group_parts);
+  *dp_columns = cols < (N + 255) / 256 ? cols * 256 : N;
   return PTDP_OK;
 }
 

@@ -151,8 +151,10 @@ size_t colsum_scratch_bytes(int rows, int width);
 int launch_colsum(int dtype, const void* in, float* out, void* scratch, int rows, int width, hipStream_t st);
 // ws / ws_bytes: optional scratch of gemm_workspace_bytes() for tiles that are split along k (may be null / 0)
 size_t gemm_workspace_bytes();
-// column tiles of C that go to the one-workgroup-per-tile launch (the rest is split along k); host only
-int gemm_split_columns(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t ws_bytes);
+// how a bf16 call is cut (host only): column tiles computed in whole rounds, then up to two groups of remainder
+// tiles, group j giving each of its tiles[j] tiles to parts[j] workgroups that split the k range evenly
+void gemm_plan_query(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t ws_bytes, int* dp_cols,
+                     int* n_groups, int* tiles, int* parts);
 int launch_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N,
                 int K, int out_f32, int accumulate, void* ws, size_t ws_bytes, hipStream_t st);
 // two fp32-accumulating weight gradients C += A^T B with the same K (bf16: one launch)

@@ -387,61 +387,77 @@ gemm_bf16_dp_pair_kernel(GemmArgs g0, void* C0, GemmArgs g1, void* C1, int n0) {
   else gemm_dp_tile<TA, TB, OUT, WGM, WGN>(g1, C1, blockIdx.x - n0, smem);
 }
 
-// "Stream-K" form for a tile count that does not fill the machine evenly: the (tile, k-tile) iteration
-// space is cut into gridDim.x equal contiguous ranges, one per workgroup.  A range shorter than one
-// tile's k extent touches at most two tiles; the workgroup stores its partial tile(s) as dense
-// 256 x 256 fp32 slabs (slab 0: the tile its range starts in, slab 1: the next one).  No workgroup
-// waits for another one and nothing is added atomically: gemm_sk_reduce_kernel sums the slabs of each
-// tile in workgroup order, so the result does not depend on timing.
+// Remainder form, for the tiles that do not fill a whole round of the machine.  The remaining tiles are cut into
+// at most two groups; a group of s tiles gives each tile to g = floor(CUs / s) workgroups, workgroup (tile, part)
+// taking k-steps [nk*part/g, nk*(part+1)/g) of its tile.  All workgroups of one part index walk the same k-range
+// at the same time, so neighbouring tiles share their operand panels through an XCD's L2 exactly as whole rounds
+// do (ranges that start at unrelated k, one per workgroup, share nothing: every panel then streams from memory
+// and the kernel runs at the memory system's rate instead of L2's).  With g = 1 a workgroup writes its tile
+// in the caller's output form; with g > 1 it stores a dense 256 x 256 fp32 slab (index part*s + tile inside the
+// group) and gemm_split_reduce_kernel sums a tile's g slabs in part order: no atomics, no waits between
+// workgroups, bit-reproducible.
 constexpr size_t kSlabFloats = (size_t)kBM * kBN;
+constexpr int kMaxSplitGroups = 2;
 
-__host__ __device__ inline long long sk_begin(long long total, int blk, int nblk) { return total * blk / nblk; }
+struct SplitPlan {
+  int dp_cols;                      // column tiles computed in whole rounds, one workgroup per tile
+  int n_groups;                     // groups of remainder tiles (0 .. kMaxSplitGroups)
+  int tiles[kMaxSplitGroups];       // tiles of each group (remainder tiles are numbered row tile fastest)
+  int parts[kMaxSplitGroups];       // workgroups per tile
+};
+// device view of the groups: first workgroup, first tile and first slab of each
+struct SplitGroups {
+  int n;
+  int tiles[kMaxSplitGroups], parts[kMaxSplitGroups], block0[kMaxSplitGroups], tile0[kMaxSplitGroups], slab0[kMaxSplitGroups];
+};
+static inline int split_blocks(int tiles, int parts) { return 8 * ((tiles * parts + 7) / 8); }   // 8 XCD queues of equal length
 
-template <bool TA, bool TB, int WGM, int WGN>
+template <bool TA, bool TB, int OUT, int WGM, int WGN>
 __global__ void __launch_bounds__(WGM * WGN * 64)
-gemm_bf16_sk_kernel(GemmArgs g, float* slabs) {
+gemm_bf16_split_kernel(GemmArgs g, void* Cv, float* slabs, SplitGroups sg) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int tiles_m = (g.M + kBM - 1) / kBM, tiles_n = (g.N + kBN - 1) / kBN;
+  int j = 0;
+  if (sg.n > 1 && (int)blockIdx.x >= sg.block0[1]) j = 1;
+  const int id = (int)blockIdx.x - sg.block0[j];
+  const int s = sg.tiles[j], parts = sg.parts[j], units = s * parts;
+  // each XCD takes a contiguous run of units in part-major order: one part index (or two), neighbouring tiles
+  const int per_xcd = (units + 7) / 8;
+  const int unit = (id & 7) * per_xcd + (id >> 3);
+  if ((id >> 3) >= per_xcd || unit >= units) return;
+  const int part = unit / s, t = unit % s;
+  const int tiles_m = (g.M + kBM - 1) / kBM;
+  const int tile = sg.tile0[j] + t;
+  const int m0 = (tile % tiles_m) * kBM, n0 = (tile / tiles_m) * kBN;
   const int nk = (g.K + BK - 1) / BK;
-  const long long total = (long long)tiles_m * tiles_n * nk;
-  long long it = sk_begin(total, blockIdx.x, gridDim.x);
-  const long long it_end = sk_begin(total, blockIdx.x + 1, gridDim.x);
-  for (int seg = 0; it < it_end && seg < 2; ++seg) {
-    const int tile = (int)(it / nk), kt0 = (int)(it % nk);
-    const int kt1 = (int)min((long long)nk, kt0 + (it_end - it));
-    const int m0 = (tile % tiles_m) * kBM, n0 = (tile / tiles_m) * kBN;
-    f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
-    zero_acc(acc);
-    gemm_mainloop<TA, TB, WGM, WGN>(acc, g, m0, n0, kt0, kt1, smem);
-    gemm_epilogue<OUT_F32_STORE, WGM, WGN>(acc, slabs + ((size_t)blockIdx.x * 2 + seg) * kSlabFloats, kBN, nullptr, kBM, kBN,
-                                           0, 0, smem);
-    it += kt1 - kt0;
-  }
+  const int kt0 = (int)((long long)nk * part / parts), kt1 = (int)((long long)nk * (part + 1) / parts);
+  f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
+  zero_acc(acc);
+  if (kt1 > kt0) gemm_mainloop<TA, TB, WGM, WGN>(acc, g, m0, n0, kt0, kt1, smem);
+  if (parts == 1)
+    gemm_epilogue<OUT, WGM, WGN>(acc, Cv, g.ldc, g.bias, g.M, g.N, m0, n0, smem);
+  else
+    gemm_epilogue<OUT_F32_STORE, WGM, WGN>(acc, slabs + (size_t)(sg.slab0[j] + unit) * kSlabFloats, kBN, nullptr, kBM, kBN, 0, 0,
+                                           smem);
 }
 
-// One workgroup per (tile, 16-row band): sums the slabs that cover the tile, in workgroup order, and
-// writes C = sum (+ bias) as bf16, or C += sum as fp32.  nblk is the grid size of the stream-K launch.
+// One workgroup per (tile of a split group, 16-row band): sums the tile's slabs in part order and writes
+// C = sum (+ bias) as bf16, or C += sum as fp32.  `first` = number of (tile, band) workgroups of group 0.
 template <bool OUT_F32>
 __global__ void __launch_bounds__(256)
-gemm_sk_reduce_kernel(const float* __restrict__ slabs, void* Cv, const bf16_t* __restrict__ bias, int M, int N, int K,
-                      size_t ldc, int nblk) {
-  const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
-  const int nk = (K + BK - 1) / BK;
-  const long long total = (long long)tiles_m * tiles_n * nk;
-  const int tile = blockIdx.x >> 4, band = blockIdx.x & 15;
+gemm_split_reduce_kernel(const float* __restrict__ slabs, void* Cv, const bf16_t* __restrict__ bias, int M, int N, size_t ldc,
+                         SplitGroups sg, int j0, int first) {
+  int j = j0, b = (int)blockIdx.x;
+  if (b >= first) { j = j0 + 1; b -= first; }
+  const int t = b >> 4, band = b & 15;
+  const int s = sg.tiles[j], parts = sg.parts[j];
+  const int tiles_m = (M + kBM - 1) / kBM;
+  const int tile = sg.tile0[j] + t;
   const int row = band * 16 + (threadIdx.x >> 4), c4 = (threadIdx.x & 15) * 4;   // 16 rows x 64 float4 per pass
-  const long long t0 = (long long)tile * nk, t1 = t0 + nk;
-  int blk = (int)(t0 * nblk / total);
-  if (blk > 0) --blk;
-  while (sk_begin(total, blk + 1, nblk) <= t0) ++blk;   // first workgroup whose range reaches into the tile
   float4 sum[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) sum[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (; blk < nblk && sk_begin(total, blk, nblk) < t1; ++blk) {
-    const long long b0 = sk_begin(total, blk, nblk);
-    if (sk_begin(total, blk + 1, nblk) == b0) continue;               // empty range
-    const int seg = (b0 / nk == tile) ? 0 : 1;
-    const float* slab = slabs + ((size_t)blk * 2 + seg) * kSlabFloats + (size_t)row * kBN + c4;
+  for (int part = 0; part < parts; ++part) {
+    const float* slab = slabs + (size_t)(sg.slab0[j] + part * s + t) * kSlabFloats + (size_t)row * kBN + c4;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const float4 v = *reinterpret_cast<const float4*>(slab + q * 64);
@@ -459,15 +475,15 @@ gemm_sk_reduce_kernel(const float* __restrict__ slabs, void* Cv, const bf16_t* _
       const float4 o = *c;
       *c = make_float4(o.x + sum[q].x, o.y + sum[q].y, o.z + sum[q].z, o.w + sum[q].w);
     } else {
-      float b[4] = {0.f, 0.f, 0.f, 0.f};
+      float b4[4] = {0.f, 0.f, 0.f, 0.f};
       if (bias) {
         const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
-        b[0] = __uint_as_float(bb.x << 16); b[1] = __uint_as_float(bb.x & 0xffff0000u);
-        b[2] = __uint_as_float(bb.y << 16); b[3] = __uint_as_float(bb.y & 0xffff0000u);
+        b4[0] = __uint_as_float(bb.x << 16); b4[1] = __uint_as_float(bb.x & 0xffff0000u);
+        b4[2] = __uint_as_float(bb.y << 16); b4[3] = __uint_as_float(bb.y & 0xffff0000u);
       }
       uint2 o;
-      o.x = pack_bf16x2(sum[q].x + b[0], sum[q].y + b[1]);
-      o.y = pack_bf16x2(sum[q].z + b[2], sum[q].w + b[3]);
+      o.x = pack_bf16x2(sum[q].x + b4[0], sum[q].y + b4[1]);
+      o.y = pack_bf16x2(sum[q].z + b4[2], sum[q].w + b4[3]);
       *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + (size_t)m * ldc + n) = o;
     }
   }
@@ -484,12 +500,12 @@ static int launch_dp(const GemmArgs& g, void* C, hipStream_t st) {
   return PTDP_OK;
 }
 
-template <bool TA, bool TB>
-static int launch_sk(const GemmArgs& g, float* slabs, int blocks, hipStream_t st) {
-  auto kern = gemm_bf16_sk_kernel<TA, TB, kWGM, kWGN>;
+template <bool TA, bool TB, int OUT>
+static int launch_split(const GemmArgs& g, void* C, float* slabs, const SplitGroups& sg, int blocks, hipStream_t st) {
+  auto kern = gemm_bf16_split_kernel<TA, TB, OUT, kWGM, kWGN>;
   static bool done[kMaxDevices] = {};
   if (set_dynamic_smem(reinterpret_cast<const void*>(kern), kGemmSmem, done) != PTDP_OK) return PTDP_E_HIP;
-  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, slabs);
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, C, slabs, sg);
   return PTDP_OK;
 }
 
@@ -505,33 +521,75 @@ static int compute_units() {
   return cu;
 }
 
-size_t gemm_workspace_bytes() { return (size_t)compute_units() * 2 * kSlabFloats * sizeof(float); }
+// every split group stores at most one slab per compute unit
+size_t gemm_workspace_bytes() { return (size_t)compute_units() * kMaxSplitGroups * kSlabFloats * sizeof(float); }
 
-// How many of the 256-column tiles of C go to the one-workgroup-per-tile launch; the rest (fewer tiles
-// than compute units, so that one workgroup's k-range never reaches into a third tile) is split along k.
-// Splitting the last round along k saves the idle share of that round and costs two more launches plus
-// a round trip of the partial tiles through memory.  Fitted to measurements: about 1.8 us per k-step,
-// 15 us fixed + 0.23 us per remainder tile; with C accumulated in fp32 the extra pass over C makes it pay
-// only for long k.
-int gemm_split_columns(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t ws_bytes) {
+// How a call is cut: whole rounds of tiles (whole columns of tiles, so that the remainder is fewer tiles than
+// compute units), then the remainder in at most two groups (see gemm_bf16_split_kernel).  A first group of
+// 2^a tiles is taken while one group over all remaining tiles would leave more than a tenth of the
+// compute units idle; the second group takes what is left.  The split is used when a cost model fitted to
+// measurements (1.8 us per k-step; 12 us per group for its first loads and last stores; 0.12 us per slab
+// for its trip through memory, 0.3 us when the sums are added into an fp32 C; 8 us for the reduce launch) puts it
+// below nine tenths of one more round of whole tiles.
+SplitPlan gemm_plan(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t ws_bytes) {
   const int ncu = compute_units();
   const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN, nk = (K + BK - 1) / BK;
   const long long tiles = (long long)tiles_m * tiles_n;
-  const int rem = (int)(tiles % ncu);
-  const bool sk_out_ok = (out_f32 && accumulate && !has_bias) || !out_f32;
-  const double sk_saved_us = (1.0 - (double)rem / ncu) * nk * 1.8;
-  const double sk_cost_us = 15.0 + rem * (out_f32 ? 0.6 : 0.23);
-  if (!(ws_bytes >= gemm_workspace_bytes() && sk_out_ok && rem != 0 && sk_saved_us > sk_cost_us && (!out_f32 || nk >= 64)))
-    return tiles_n;
-  // whole columns only: the full rounds' tiles, rounded up to a column boundary, so that fewer than
-  // ncu tiles remain (rounding down would leave up to tiles_m - 1 more)
+  SplitPlan P;
+  P.dp_cols = tiles_n;
+  P.n_groups = 0;
+  for (int j = 0; j < kMaxSplitGroups; ++j) P.tiles[j] = P.parts[j] = 0;
+  const bool out_ok = (out_f32 && accumulate && !has_bias) || !out_f32;
+  if (tiles % ncu == 0 || !out_ok || ws_bytes < gemm_workspace_bytes() || (out_f32 && nk < 64)) return P;
+  // whole columns only: the full rounds' tiles, rounded up to a column boundary
   const long long full = (tiles / ncu) * ncu;
   const int dp_cols = (int)((full + tiles_m - 1) / tiles_m);
-  return dp_cols < tiles_n ? dp_cols : tiles_n;
+  int rem = (int)(tiles - (long long)dp_cols * tiles_m);
+  if (dp_cols >= tiles_n || rem <= 0 || rem >= ncu) return P;
+  int gt[kMaxSplitGroups], gp[kMaxSplitGroups], n = 0;
+  while (rem > 0 && n < kMaxSplitGroups) {
+    int take = rem;
+    if (n + 1 < kMaxSplitGroups && (long long)rem * (ncu / rem) * 10 < (long long)ncu * 9) {
+      take = 1;
+      while (take * 2 <= rem) take *= 2;
+    }
+    gt[n] = take;
+    gp[n] = ncu / take < nk ? ncu / take : nk;   // never more parts than k-steps
+    if (gp[n] < 1) gp[n] = 1;
+    rem -= take;
+    ++n;
+  }
+  double t_split = 0.0;
+  bool any = false;
+  for (int j = 0; j < n; ++j) {
+    t_split += 1.8 * ((nk + gp[j] - 1) / gp[j]) + 12.0;
+    if (gp[j] > 1) {
+      t_split += (out_f32 ? 0.3 : 0.12) * gt[j] * gp[j];
+      any = true;
+    }
+  }
+  if (any) t_split += 8.0;
+  if (!any || t_split >= 0.9 * 1.8 * nk) return P;
+  P.dp_cols = dp_cols;
+  P.n_groups = n;
+  for (int j = 0; j < n; ++j) {
+    P.tiles[j] = gt[j];
+    P.parts[j] = gp[j];
+  }
+  return P;
 }
 
-// Splits the columns into a part whose tiles fill whole rounds of the machine (one workgroup per tile)
-// and a remainder of less than one round that is spread evenly over all compute units in stream-K form.
+void gemm_plan_query(int M, int N, int K, int out_f32, int accumulate, int has_bias, size_t ws_bytes, int* dp_cols,
+                     int* n_groups, int* tiles, int* parts) {
+  const SplitPlan P = gemm_plan(M, N, K, out_f32, accumulate, has_bias, ws_bytes);
+  *dp_cols = P.dp_cols;
+  *n_groups = P.n_groups;
+  for (int j = 0; j < kMaxSplitGroups; ++j) {
+    tiles[j] = P.tiles[j];
+    parts[j] = P.parts[j];
+  }
+}
+
 template <bool TA, bool TB>
 static int launch_bf16_mode(const void* A, const void* B, void* C, const void* bias, int M, int N, int K, int out_f32,
                             int accumulate, void* ws, size_t ws_bytes, hipStream_t st) {
@@ -548,10 +606,10 @@ static int launch_bf16_mode(const void* A, const void* B, void* C, const void* b
   g.ldb = TB ? (size_t)N : (size_t)K;
   g.ldc = (size_t)N;
 
-  const int dp_cols = gemm_split_columns(M, N, K, out_f32, accumulate, bias != nullptr, ws != nullptr ? ws_bytes : 0);
+  const SplitPlan P = gemm_plan(M, N, K, out_f32, accumulate, bias != nullptr, ws != nullptr ? ws_bytes : 0);
   const int ncu = compute_units();
   const int tiles_m = (M + kBM - 1) / kBM, tiles_n = (N + kBN - 1) / kBN;
-  const int n_dp = dp_cols < tiles_n ? dp_cols * kBN : N;
+  const int n_dp = P.dp_cols < tiles_n ? P.dp_cols * kBN : N;
   if (n_dp > 0) {
     GemmArgs d = g;
     d.N = n_dp;
@@ -562,19 +620,50 @@ static int launch_bf16_mode(const void* A, const void* B, void* C, const void* b
     if (rc != PTDP_OK) return rc;
   }
   if (n_dp < N) {
+    // the remainder as a problem of its own: columns n_dp .. N-1
     GemmArgs r = g;
     r.N = N - n_dp;
     r.B = TB ? g.B + n_dp : g.B + (size_t)n_dp * K;
-    const int sk_tiles = tiles_m * ((r.N + kBN - 1) / kBN);
-    if (sk_tiles > ncu) return PTDP_E_STATE;   // a workgroup's range would span more than two tiles
-    const int rc = launch_sk<TA, TB>(r, (float*)ws, ncu, st);
+    r.bias = bias ? (const bf16_t*)bias + n_dp : nullptr;
+    void* Cr = out_f32 ? (void*)((float*)C + n_dp) : (void*)((bf16_t*)C + n_dp);
+    SplitGroups sg;
+    sg.n = P.n_groups;
+    int blocks = 0, tile0 = 0, slab0 = 0;
+    for (int j = 0; j < kMaxSplitGroups; ++j) {
+      sg.tiles[j] = j < P.n_groups ? P.tiles[j] : 0;
+      sg.parts[j] = j < P.n_groups ? P.parts[j] : 1;
+      sg.block0[j] = blocks;
+      sg.tile0[j] = tile0;
+      sg.slab0[j] = slab0;
+      if (j < P.n_groups) {
+        if (P.tiles[j] * P.parts[j] > ncu) return PTDP_E_STATE;   // a group never needs more than one slab per compute unit
+        blocks += split_blocks(P.tiles[j], P.parts[j]);
+        tile0 += P.tiles[j];
+        if (P.parts[j] > 1) slab0 += P.tiles[j] * P.parts[j];
+      }
+    }
+    if (tile0 != tiles_m * ((r.N + kBN - 1) / kBN)) return PTDP_E_STATE;   // the groups cover the remainder exactly
+    int rc;
+    if (!out_f32) rc = launch_split<TA, TB, OUT_BF16>(r, Cr, (float*)ws, sg, blocks, st);
+    else if (accumulate) rc = launch_split<TA, TB, OUT_F32_RMW>(r, Cr, (float*)ws, sg, blocks, st);
+    else rc = launch_split<TA, TB, OUT_F32_STORE>(r, Cr, (float*)ws, sg, blocks, st);
     if (rc != PTDP_OK) return rc;
-    if (out_f32)
-      hipLaunchKernelGGL(gemm_sk_reduce_kernel<true>, dim3(sk_tiles * 16), dim3(256), 0, st, (const float*)ws,
-                         (void*)((float*)C + n_dp), (const bf16_t*)nullptr, M, r.N, K, (size_t)N, ncu);
-    else
-      hipLaunchKernelGGL(gemm_sk_reduce_kernel<false>, dim3(sk_tiles * 16), dim3(256), 0, st, (const float*)ws,
-                         (void*)((bf16_t*)C + n_dp), bias ? (const bf16_t*)bias + n_dp : nullptr, M, r.N, K, (size_t)N, ncu);
+    // one reduce launch over the groups that were split (they are adjacent: a group with one part comes last, if at all)
+    int j0 = -1, first = 0, total = 0;
+    for (int j = 0; j < P.n_groups; ++j) {
+      if (P.parts[j] <= 1) continue;
+      if (j0 < 0) { j0 = j; first = P.tiles[j] * 16; }
+      else if (j != j0 + 1) return PTDP_E_STATE;
+      total += P.tiles[j] * 16;
+    }
+    if (j0 >= 0) {
+      if (out_f32)
+        hipLaunchKernelGGL(gemm_split_reduce_kernel<true>, dim3(total), dim3(256), 0, st, (const float*)ws, Cr,
+                           (const bf16_t*)nullptr, M, r.N, (size_t)N, sg, j0, first);
+      else
+        hipLaunchKernelGGL(gemm_split_reduce_kernel<false>, dim3(total), dim3(256), 0, st, (const float*)ws, Cr, r.bias, M, r.N,
+                           (size_t)N, sg, j0, first);
+    }
   }
   return PTDP_OK;
 }

@@ -163,45 +163,49 @@ def test_batch_time_matches_oracle_and_rejects_bad_input():
 
 def _plan(M, N, K, out_f32=0, accumulate=0, has_bias=0, ws=None):
     ws = B.ptdp_gemm_workspace_bytes() if ws is None else ws
-    d, t, g = C.c_int(0), C.c_int(0), C.c_int(0)
-    assert B.ptdp_gemm_plan(M, N, K, out_f32, accumulate, has_bias, ws, C.byref(d), C.byref(t), C.byref(g)) == B.OK
-    return d.value, t.value, g.value
+    d, n = C.c_int(0), C.c_int(0)
+    tiles, parts = (C.c_int * 2)(), (C.c_int * 2)()
+    assert B.ptdp_gemm_plan(M, N, K, out_f32, accumulate, has_bias, ws, C.byref(d), C.byref(n), tiles, parts) == B.OK
+    return d.value, [(tiles[j], parts[j]) for j in range(n.value)]
 
 
-def test_gemm_k_split_covers_every_k_step_once():
-    """The remainder tiles of a GEMM are cut into equal contiguous (tile, k-step) ranges, one per workgroup,
-    and a workgroup handles at most two tiles: replay that arithmetic on the host for shapes whose row-tile
-    count does not divide the number of compute units, and count how often each k-step is taken."""
-    shapes = [(14336, 12800, 51200), (26624, 11264, 33792), (2048, 9600, 25600), (2048, 25600, 12800),
-              (2048, 4608, 12288), (8192, 6144, 2048), (14336, 12800, 4096), (7 * 256, 37 * 256, 8192),
-              (56 * 256, 5 * 256, 16384), (3 * 256, 87 * 256, 6400), (8, 264 * 256, 4096), (2048 + 8, 9600 + 8, 25600 + 8)]
+def test_gemm_remainder_split_covers_every_tile_and_k_step_once():
+    """Tiles beyond the whole rounds go to at most two groups; every tile of a group is shared by `parts`
+    workgroups with contiguous, disjoint k-ranges: replay that arithmetic on the host, also for shapes whose
+    row-tile count does not divide the number of compute units, and count how often each k-step is taken."""
+    ncu = B.ptdp_gemm_workspace_bytes() // (2 * 256 * 256 * 4)
+    shapes = [(14336, 12800, 51200), (26624, 11264, 33792), (2048, 9600, 25600), (2048, 25600, 12800), (2048, 12800, 25600),
+              (2048, 3200, 25600), (2048, 4608, 12288), (8192, 6144, 2048), (14336, 1792, 4096), (7 * 256, 37 * 256, 8192),
+              (56 * 256, 5 * 256, 16384), (3 * 256, 87 * 256, 6400), (8, 264 * 256, 4096), (2048 + 8, 9600 + 8, 25600 + 8),
+              (2048, 6400, 25600), (264, 4104, 4096), (2048, 10248, 4096), (256, 256, 64), (256, 512, 128)]
     n_split = 0
     for (M, N, K) in shapes:
         for out_f32, acc in ((0, 0), (1, 1)):
-            dp_cols, sk_tiles, nblk = _plan(M, N, K, out_f32, acc)
+            dp_cols, groups = _plan(M, N, K, out_f32, acc)
             tiles_m, tiles_n, nk = -(-M // 256), -(-N // 256), -(-K // 64)
             assert dp_cols == N or dp_cols % 256 == 0
-            if sk_tiles == 0:
+            rem = tiles_m * (tiles_n - dp_cols // 256) if dp_cols < N else 0
+            if not groups:
                 assert dp_cols == N
                 continue
             n_split += 1
-            assert sk_tiles < nblk, (M, N, K, sk_tiles)
-            assert sk_tiles == tiles_m * (tiles_n - dp_cols // 256)
-            total = sk_tiles * nk
-            seen = np.zeros(total, dtype=np.int32)
-            for blk in range(nblk):
-                it, end = total * blk // nblk, total * (blk + 1) // nblk
-                for seg in range(2):                      # the kernel's loop: at most two partial tiles
-                    if it >= end:
-                        break
-                    kt0 = it % nk
-                    kt1 = min(nk, kt0 + (end - it))
-                    seen[it:it + kt1 - kt0] += 1
-                    it += kt1 - kt0
-                assert it == end, (M, N, K, blk)
+            assert 0 < rem < ncu and sum(t for t, _ in groups) == rem, (M, N, K, groups)
+            assert any(p > 1 for _, p in groups)
+            seen = np.zeros((rem, nk), dtype=np.int32)
+            tile0 = 0
+            for (t, p) in groups:
+                assert t >= 1 and 1 <= p <= nk and t * p <= ncu, (M, N, K, groups)
+                for tile in range(t):
+                    for part in range(p):
+                        seen[tile0 + tile, nk * part // p: nk * (part + 1) // p] += 1
+                tile0 += t
             assert (seen == 1).all(), (M, N, K)
-    assert n_split >= 6
-    assert _plan(14336, 12800, 51200, ws=0) == (12800, 0, 256)        # no workspace: never split
+    assert n_split >= 8
+    assert _plan(14336, 12800, 51200, ws=0) == (12800, [])            # no workspace: never split
+    # the layer shapes of the 1T-shaped shard: 144 remainder tiles -> 128 tiles on 2 workgroups each + 16 tiles on 16
+    assert _plan(2048, 12800, 25600) == (8192, [(128, 2), (16, 16)])
+    assert _plan(2048, 9600, 25600) == (8192, [(48, 5)])
+    assert _plan(2048, 3200, 25600) == (0, [(64, 4), (40, 6)])
 
 
 def test_cfg_refuses_operands_beyond_the_gemm_offset_range():
