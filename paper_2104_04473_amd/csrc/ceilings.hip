@@ -47,8 +47,21 @@ __global__ void __launch_bounds__(512) mfma_ceiling_kernel(float* sink, int iter
   if (s == 123.456f) sink[0] = s;   // keeps the loop alive without a store on the usual path
 }
 
-__global__ void __launch_bounds__(256) copy_ceiling_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+// Each workgroup copies one contiguous run, four 16-byte loads per lane in flight, non-temporal accesses: the
+// fastest of the forms tried (a grid-wide stride with one access per lane in flight reaches 4.6 TB/s, this 5.5).
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) copy_ceiling_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst, size_t n) {
+  const size_t per = (n + gridDim.x - 1) / gridDim.x;
+  const size_t b0 = (size_t)blockIdx.x * per, b1 = min(n, b0 + per);
+  size_t i = b0 + threadIdx.x;
+  for (; i + 3 * 256 < b1; i += 4 * 256) {
+    u32x4_t v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) __builtin_nontemporal_store(v[u], dst + i + u * 256);
+  }
+  for (; i < b1; i += 256) dst[i] = src[i];
 }
 
 }  // namespace ptdp
@@ -72,7 +85,7 @@ int ptdp_ceiling_copy(const void* src, void* dst, size_t bytes, void* stream) {
   if (!src || !dst) return PTDP_E_NULL_PTR;
   if (bytes % 16 != 0 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return PTDP_E_INVALID_ARG;
   if (bytes == 0) return PTDP_OK;
-  hipLaunchKernelGGL(copy_ceiling_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst,
+  hipLaunchKernelGGL(copy_ceiling_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const u32x4_t*)src, (u32x4_t*)dst,
                      bytes / 16);
   return hipGetLastError() == hipSuccess ? PTDP_OK : PTDP_E_HIP;
 }
