@@ -345,7 +345,7 @@ int ptdp_layernorm_fwd(int dtype, const void* x, const void* gain, const void* b
                        float* rstd, void* x_copy, int rows, int width, float eps, void* stream);
 /* dx = resid + LN'(du): resid [rows,width] may be NULL (treated as 0), dx may
  * alias resid or du.  dgain, dbias [width] fp32 +=.  scratch: dev,
- * >= ptdp_colsum_scratch_bytes(rows, 2*width). */
+ * >= ptdp_layernorm_bwd_scratch_bytes(rows, width). */
 int ptdp_layernorm_bwd(int dtype, const void* du, const void* x, const void* gain, const float* mu,
                        const float* rstd, const void* resid, void* dx, float* dgain, float* dbias,
                        void* scratch, int rows, int width, void* stream);
@@ -365,6 +365,7 @@ int ptdp_bias_dropout_add_bwd(int dtype, const void* dout, void* din, float* dbi
                               int width, float p, uint64_t seed, uint32_t layer, uint32_t site,
                               uint64_t microbatch, void* stream);
 size_t ptdp_colsum_scratch_bytes(int rows, int width);
+size_t ptdp_layernorm_bwd_scratch_bytes(int rows, int width);
 /* For callers that cannot allocate device memory (code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): ptdp_bias_dropout_add_bwd
  * without the scratch argument.  The column-sum partials live in a static device

@@ -109,6 +109,7 @@ SIGNATURES = {
     "ptdp_bias_dropout_add_bwd_noalloc": (_i, [_i, _vp, _vp, _vp, _i, _i, _f, _u64, _u32, _u32, _u64, _vp]),
     "ptdp_noalloc_scratch_bytes": (_sz, []),
     "ptdp_colsum_scratch_bytes": (_sz, [_i, _i]),
+    "ptdp_layernorm_bwd_scratch_bytes": (_sz, [_i, _i]),
     "ptdp_dropout_mask": (_i, [_vp, _i64, _f, _u64, _u32, _u32, _u64, _vp]),
     "ptdp_gemm": (_i, [_i, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "ptdp_gemm_workspace_bytes": (_sz, []),

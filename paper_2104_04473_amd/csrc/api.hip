@@ -142,7 +142,9 @@ static WsLayout ws_layout(const ptdp_layer_cfg* c) {
   sz[WS_CTX] = d.T * d.hp * d.esz;
   sz[WS_QKV] = d.T * 3 * d.hp * d.esz;
   sz[WS_DELTA] = (size_t)c->b * d.al * c->s * sizeof(float);
-  size_t cs = colsum_scratch_bytes((int)d.T, (int)(2 * d.h));
+  size_t cs = layernorm_bwd_scratch_bytes((int)d.T, (int)d.h);
+  const size_t c1 = colsum_scratch_bytes((int)d.T, (int)d.h);
+  if (c1 > cs) cs = c1;
   const size_t c2 = colsum_scratch_bytes((int)d.T, (int)d.fp), c3 = colsum_scratch_bytes((int)d.T, (int)(3 * d.hp));
   if (c2 > cs) cs = c2;
   if (c3 > cs) cs = c3;
@@ -643,7 +645,7 @@ LmLayout lm_layout(const ptdp_layer_cfg* c, int vrows) {
   sz[LM_U] = sz[LM_DU] = d.T * d.h * d.esz;   // LM_DU doubles as the masked gradient of the embedding backward
   sz[LM_MU] = sz[LM_RSTD] = d.T * sizeof(float);
   sz[LM_LOGITS] = (size_t)d.T * vrows * d.esz;
-  sz[LM_COLSUM] = colsum_scratch_bytes((int)d.T, (int)(2 * d.h));
+  sz[LM_COLSUM] = layernorm_bwd_scratch_bytes((int)d.T, (int)d.h);
   sz[LM_SPLITK] = c->dtype == PTDP_BF16 ? gemm_workspace_bytes() : 0;
   LmLayout L;
   size_t o = 0;
@@ -804,6 +806,8 @@ int ptdp_bias_dropout_add_bwd_noalloc(int dtype, const void* dout, void* din, fl
 size_t ptdp_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
 
 size_t ptdp_colsum_scratch_bytes(int rows, int width) { return colsum_scratch_bytes(rows, width); }
+
+size_t ptdp_layernorm_bwd_scratch_bytes(int rows, int width) { return layernorm_bwd_scratch_bytes(rows, width); }
 
 size_t ptdp_gemm_workspace_bytes(void) { return gemm_workspace_bytes(); }
 

@@ -147,6 +147,7 @@ int launch_bda_bwd_static(int dtype, const void* dout, void* din, float* dbias, 
 bool profiling_enabled();
 int launch_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t key, hipStream_t st);
 size_t colsum_scratch_bytes(int rows, int width);
+size_t layernorm_bwd_scratch_bytes(int rows, int width);   // scratch of launch_layernorm_bwd
 // out[width] (fp32) += column sums of in[rows, width]
 int launch_colsum(int dtype, const void* in, float* out, void* scratch, int rows, int width, hipStream_t st);
 // ws / ws_bytes: optional scratch of gemm_workspace_bytes() for tiles that are split along k (may be null / 0)

@@ -70,98 +70,127 @@ __global__ void layernorm_fwd_kernel(const T* __restrict__ x, const T* __restric
   }
 }
 
-// LayerNorm backward, input gradient.  One block per row, the row of du and x lives in registers:
-//   xhat = (x-mu)*rstd, dxhat = du*gain, dx = resid + rstd*(dxhat - mean(dxhat) - xhat*mean(dxhat*xhat)).
+// LayerNorm backward: input gradient and the partial sums of the gain / bias gradients in one pass.
+//   xhat = (x-mu)*rstd, dxhat = du*gain, dx = resid + rstd*(dxhat - mean(dxhat) - xhat*mean(dxhat*xhat)),
+//   dgain[c] = sum_r du*xhat, dbias[c] = sum_r du.
+// A block walks `rpb` consecutive rows; each row of du and x is read once and waits in registers in storage
+// form (fp32 copies of both would not fit next to the column accumulators) while the two row means are reduced;
+// every lane keeps the running column sums of its own VPT*N columns and stores them once, as row blockIdx.x of
+// part[][2*width] (gain part first).  dx may alias du: a lane overwrites only elements it has read itself.
 template <typename T, int VPT>
-__global__ void layernorm_bwd_dx_kernel(const T* __restrict__ du, const T* __restrict__ x, const T* __restrict__ gain,
-                                        const float* __restrict__ mu, const float* __restrict__ rstd, const T* resid,
-                                        T* dx, int width) {
+__global__ void __launch_bounds__(512)
+layernorm_bwd_kernel(const T* du, const T* __restrict__ x, const T* __restrict__ gain, const float* __restrict__ mu,
+                     const float* __restrict__ rstd, const T* resid, T* dx, float* __restrict__ part, int rows, int width,
+                     int rpb) {
   constexpr int N = Vec16<T>::N;
-  __shared__ float red[16];
+  extern __shared__ __attribute__((aligned(16))) char ln_smem[];
+  T* gain_s = reinterpret_cast<T*>(ln_smem);   // the gain row, read twice per row of the block
+  __shared__ float red[2][16];
   const int nvec = width / N;
-  const size_t base = (size_t)blockIdx.x * width;
-  const float m = mu[blockIdx.x], rs = rstd[blockIdx.x];
-  float dxh[VPT][N], xh[VPT][N];
-  float s1 = 0.f, s2 = 0.f;
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (int c = threadIdx.x; c < nvec; c += blockDim.x) {
+    Vec16<T> g;
+    g.load(gain + (size_t)c * N);
+    g.store(gain_s + (size_t)c * N);
+  }
+  float ag[VPT][N], ab[VPT][N];
+#pragma unroll
+  for (int i = 0; i < VPT; ++i)
+#pragma unroll
+    for (int j = 0; j < N; ++j) ag[i][j] = ab[i][j] = 0.f;
+  const int r0 = blockIdx.x * rpb, r1 = min(rows, r0 + rpb);
+  for (int r = r0; r < r1; ++r) {
+    const size_t base = (size_t)r * width;
+    const float m = mu[r], rs = rstd[r];
+    Vec16<T> a[VPT], b[VPT];
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int c = threadIdx.x + i * blockDim.x;
+      if (c < nvec) {
+        a[i].load(du + base + (size_t)c * N);
+        b[i].load(x + base + (size_t)c * N);
+      }
+    }
+    __syncthreads();   // gain row visible (first row); `red` of the previous row no longer read
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int c = threadIdx.x + i * blockDim.x;
+      if (c < nvec) {
+        Vec16<T> g;
+        float af[N], xf[N], gf[N];
+        g.load(gain_s + (size_t)c * N);
+        a[i].unpack(af);
+        b[i].unpack(xf);
+        g.unpack(gf);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+          const float xh = (xf[j] - m) * rs, dxh = af[j] * gf[j];
+          s1 += dxh;
+          s2 += dxh * xh;
+          ag[i][j] += af[j] * xh;
+          ab[i][j] += af[j];
+        }
+      }
+    }
+    // both row sums through one pair of barriers
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if ((threadIdx.x & 63) == 0) {
+      red[0][wave] = s1;
+      red[1][wave] = s2;
+    }
+    __syncthreads();
+    float c1 = 0.f, c2 = 0.f;
+    for (int w = 0; w < nw; ++w) {
+      c1 += red[0][w];
+      c2 += red[1][w];
+    }
+    c1 /= (float)width;
+    c2 /= (float)width;
+    // the second pass unpacks the stored row again: keeping the first pass's fp32 values alive across the
+    // reduction instead would cost two more registers per element and spill
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      asm volatile("" : "+v"(a[i].raw.x), "+v"(a[i].raw.y), "+v"(a[i].raw.z), "+v"(a[i].raw.w));
+      asm volatile("" : "+v"(b[i].raw.x), "+v"(b[i].raw.y), "+v"(b[i].raw.z), "+v"(b[i].raw.w));
+    }
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int c = threadIdx.x + i * blockDim.x;
+      if (c < nvec) {
+        Vec16<T> g, o;
+        float af[N], xf[N], gf[N], of[N];
+        g.load(gain_s + (size_t)c * N);
+        a[i].unpack(af);
+        b[i].unpack(xf);
+        g.unpack(gf);
+        if (resid) {
+          Vec16<T> rr;
+          rr.load(resid + base + (size_t)c * N);
+          rr.unpack(of);
+        } else {
+#pragma unroll
+          for (int j = 0; j < N; ++j) of[j] = 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) of[j] += rs * (af[j] * gf[j] - c1 - (xf[j] - m) * rs * c2);
+        o.pack(of);
+        o.store(dx + base + (size_t)c * N);
+      }
+    }
+  }
+  float* prow = part + (size_t)blockIdx.x * 2 * width;
 #pragma unroll
   for (int i = 0; i < VPT; ++i) {
     const int c = threadIdx.x + i * blockDim.x;
     if (c < nvec) {
-      Vec16<T> a, b, g;
-      float gf[N];
-      a.load(du + base + (size_t)c * N);
-      b.load(x + base + (size_t)c * N);
-      g.load(gain + (size_t)c * N);
-      a.unpack(dxh[i]);
-      b.unpack(xh[i]);
-      g.unpack(gf);
 #pragma unroll
       for (int j = 0; j < N; ++j) {
-        xh[i][j] = (xh[i][j] - m) * rs;
-        dxh[i][j] *= gf[j];
-        s1 += dxh[i][j];
-        s2 += dxh[i][j] * xh[i][j];
+        prow[(size_t)c * N + j] = ag[i][j];
+        prow[(size_t)width + (size_t)c * N + j] = ab[i][j];
       }
     }
-  }
-  const float c1 = block_sum(s1, red) / (float)width;
-  const float c2 = block_sum(s2, red) / (float)width;
-#pragma unroll
-  for (int i = 0; i < VPT; ++i) {
-    const int c = threadIdx.x + i * blockDim.x;
-    if (c < nvec) {
-      float of[N];
-      if (resid) {
-        Vec16<T> rr;
-        rr.load(resid + base + (size_t)c * N);
-        rr.unpack(of);
-      } else {
-#pragma unroll
-        for (int j = 0; j < N; ++j) of[j] = 0.f;
-      }
-#pragma unroll
-      for (int j = 0; j < N; ++j) of[j] += rs * (dxh[i][j] - c1 - xh[i][j] * c2);
-      Vec16<T> o;
-      o.pack(of);
-      o.store(dx + base + (size_t)c * N);
-    }
-  }
-}
-
-// LayerNorm backward, parameter gradients: part[blockIdx.y][c] = sum_r du*xhat, part[..][width + c] = sum_r du
-// over the block's kColRows rows; thread owns one 16-byte column group.
-template <typename T>
-__global__ void layernorm_bwd_param_kernel(const T* __restrict__ du, const T* __restrict__ x,
-                                           const float* __restrict__ mu, const float* __restrict__ rstd,
-                                           float* __restrict__ part, int rows, int width) {
-  constexpr int N = Vec16<T>::N;
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= width / N) return;
-  float ag[N], ab[N];
-#pragma unroll
-  for (int j = 0; j < N; ++j) ag[j] = ab[j] = 0.f;
-  const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
-#pragma unroll 4
-  for (int r = r0; r < r1; ++r) {
-    const size_t off = (size_t)r * width + (size_t)c * N;
-    const float m = mu[r], rs = rstd[r];
-    Vec16<T> a, b;
-    float af[N], xf[N];
-    a.load(du + off);
-    b.load(x + off);
-    a.unpack(af);
-    b.unpack(xf);
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-      ag[j] += af[j] * ((xf[j] - m) * rs);
-      ab[j] += af[j];
-    }
-  }
-  float* prow = part + (size_t)blockIdx.y * 2 * width;
-#pragma unroll
-  for (int j = 0; j < N; ++j) {
-    prow[(size_t)c * N + j] = ag[j];
-    prow[(size_t)width + (size_t)c * N + j] = ab[j];
   }
 }
 
@@ -430,6 +459,15 @@ static int colsum_finish(const float* part, int nparts, int stride, float* out0,
   return L.status();
 }
 
+// rows walked by one block of the backward kernel: at most 256 blocks (one per compute unit of an MI355X)
+static inline int ln_bwd_rows_per_block(int rows) { return rows > 256 ? (rows + 255) / 256 : 1; }
+
+size_t layernorm_bwd_scratch_bytes(int rows, int width) {
+  if (rows <= 0 || width <= 0) return 0;
+  const int rpb = ln_bwd_rows_per_block(rows);
+  return (size_t)((rows + rpb - 1) / rpb) * 2 * (size_t)width * sizeof(float);
+}
+
 template <typename T>
 static int ln_bwd_t(const void* du, const void* x, const void* gain, const float* mu, const float* rstd,
                     const void* resid, void* dx, float* dgain, float* dbias, void* scratch, int rows, int width,
@@ -438,31 +476,29 @@ static int ln_bwd_t(const void* du, const void* x, const void* gain, const float
   int vpt;
   const int threads = ln_threads(width / N, &vpt);
   if (vpt > 8) return PTDP_E_UNSUPPORTED;
+  vpt = (width / N + threads - 1) / threads;   // exact count: every vector slot costs two column accumulators
   float* part = (float*)scratch;
-  const dim3 pgrid((width / N + 255) / 256, (rows + kColRows - 1) / kColRows);
-  {
-    // the parameter gradients read du before dx may overwrite it (dx may alias du)
-    Launch L(PTDP_K_LN_BWD, (double)rows * width * sizeof(T) * 2, st);
-    hipLaunchKernelGGL((layernorm_bwd_param_kernel<T>), pgrid, dim3(256), 0, st, (const T*)du, (const T*)x, mu, rstd,
-                       part, rows, width);
-    if (L.status() != PTDP_OK) return L.status();
-  }
+  const int rpb = ln_bwd_rows_per_block(rows), nblk = (rows + rpb - 1) / rpb;
   {
     const double bytes = (double)rows * width * sizeof(T) * (resid ? 4 : 3);
     Launch L(PTDP_K_LN_BWD, bytes, st);
-#define PTDP_LN_BWD(V)                                                                                           \
-  hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), dim3(rows), dim3(threads), 0, st, (const T*)du, (const T*)x, \
-                     (const T*)gain, mu, rstd, (const T*)resid, (T*)dx, width)
+#define PTDP_LN_BWD(V)                                                                                        \
+  hipLaunchKernelGGL((layernorm_bwd_kernel<T, V>), dim3(nblk), dim3(threads), (size_t)width * sizeof(T), st, (const T*)du, (const T*)x, \
+                     (const T*)gain, mu, rstd, (const T*)resid, (T*)dx, part, rows, width, rpb)
     switch (vpt) {
       case 1: PTDP_LN_BWD(1); break;
       case 2: PTDP_LN_BWD(2); break;
+      case 3: PTDP_LN_BWD(3); break;
       case 4: PTDP_LN_BWD(4); break;
+      case 5: PTDP_LN_BWD(5); break;
+      case 6: PTDP_LN_BWD(6); break;
+      case 7: PTDP_LN_BWD(7); break;
       default: PTDP_LN_BWD(8); break;
     }
 #undef PTDP_LN_BWD
     if (L.status() != PTDP_OK) return L.status();
   }
-  return colsum_finish(part, pgrid.y, 2 * width, dgain, dbias, width, st);
+  return colsum_finish(part, nblk, 2 * width, dgain, dbias, width, st);
 }
 
 int launch_layernorm_bwd(int dtype, const void* du, const void* x, const void* gain, const float* mu,

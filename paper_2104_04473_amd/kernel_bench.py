@@ -74,7 +74,7 @@ def main():
            [lambda i=i: B.ptdp_layernorm_fwd(B.BF16, xs[i].data_ptr(), g.data_ptr(), be.data_ptr(), us[i].data_ptr(),
                                              mu.data_ptr(), rstd.data_ptr(), None, T, h, 1e-5, sh) for i in range(n)])
     dg = torch.zeros(h, device=dev); db = torch.zeros(h, device=dev)
-    scratch = torch.empty(B.ptdp_colsum_scratch_bytes(T, 2 * max(h, fp)), dtype=torch.uint8, device=dev)
+    scratch = torch.empty(max(B.ptdp_layernorm_bwd_scratch_bytes(T, h), B.ptdp_colsum_scratch_bytes(T, max(h, fp))), dtype=torch.uint8, device=dev)
     B.ptdp_layernorm_fwd(B.BF16, xs[0].data_ptr(), g.data_ptr(), be.data_ptr(), us[0].data_ptr(), mu.data_ptr(),
                          rstd.data_ptr(), None, T, h, 1e-5, sh)
     report("layernorm_bwd (dx + parameter gradients, with residual)", T * h * 12, "GB/s",

@@ -44,7 +44,7 @@ def test_layernorm_forward_backward(dtype, rows, width):
     assert torch.equal(xc, x)
 
     dg = torch.full((width,), 1.0, device="cuda"); db = torch.full((width,), -2.0, device="cuda")   # += semantics
-    scratch = dev_bytes(B.ptdp_colsum_scratch_bytes(rows, 2 * width))
+    scratch = dev_bytes(B.ptdp_layernorm_bwd_scratch_bytes(rows, width))
     dx = torch.empty_like(x)
     B.check(B.ptdp_layernorm_bwd(dtype, du.data_ptr(), x.data_ptr(), gain.data_ptr(), mu.data_ptr(), rstd.data_ptr(),
                                  resid.data_ptr(), dx.data_ptr(), dg.data_ptr(), db.data_ptr(), scratch.data_ptr(),
