@@ -15,6 +15,7 @@ namespace ptdp {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
 // ------------------------------------------------------------------------------------------------
 // fp32: 64 x 64 x 16 tile, 256 threads, 4 x 4 outputs per thread, generic strides.
@@ -146,6 +147,29 @@ __device__ __forceinline__ bf16x8_t read_frag(const char* tile, int row_base, in
     const int r = lane & 15, G = lane >> 4;
     const int n0 = row_base + 16 * (G & 1) + 4 * (r & 3);
     const int k = kk * 16 + 8 * (G >> 1) + (r >> 2);  // (k & 3) == r >> 2 for both halves
+    const int slot = (n0 >> 3) ^ (4 * (r >> 2));
+    const char* p = tile + k * 512 + slot * 16 + (n0 & 7) * 2;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p + 4 * 512));
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8_t;
+    s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return *reinterpret_cast<bf16x8_t*>(&v);
+  }
+}
+
+// MFMA operand fragment of v_mfma_f32_16x16x32_bf16 from either layout: lane (lane & 15) is the tile row
+// (column of C for the B operand) inside the 16-row block starting at row_base, lane >> 4 selects which 8 of
+// the 32 k of step ks (0, 1) the lane carries.
+template <bool KSLOW>
+__device__ __forceinline__ bf16x8_t read_frag16(const char* tile, int row_base, int ks, int lane) {
+  if (!KSLOW) {
+    const int row = row_base + (lane & 15);
+    const int chunk = (ks * 4 + (lane >> 4)) ^ ((row >> 1) & 7);
+    return *reinterpret_cast<const bf16x8_t*>(tile + row * 128 + chunk * 16);
+  } else {
+    const int r = lane & 15, G = lane >> 4;
+    const int n0 = row_base + 4 * (r & 3);
+    const int k = ks * 32 + 8 * G + (r >> 2);  // (k & 3) == r >> 2 for both halves
     const int slot = (n0 >> 3) ^ (4 * (r >> 2));
     const char* p = tile + k * 512 + slot * 16 + (n0 & 7) * 2;
     const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
@@ -290,7 +314,6 @@ __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[kBM / WGM / 
   }
   const int c4 = (lane & 15) * 4;            // first of this lane's 4 columns inside the wave's 64
   const int n = n0 + wn0 + c4;
-  typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
   // Gradient accumulators are touched once per launch: stream them past the caches.  The old values of
   // slab i + 1 are requested before slab i is staged and added, so two slabs of loads are in flight.
   f32x4_t old[2][8];
@@ -345,6 +368,190 @@ template <int TM, int TN> __device__ __forceinline__ void zero_acc(f32x16_t (&ac
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 }
 
+// ---- the same main loop and output stage on v_mfma_f32_16x16x32_bf16 -------------------------------------------
+// On operands that change from instruction to instruction the chip sustains about a tenth more with this
+// shape than with 32x32x16 (a register-resident loop: 2.08-2.13 against 1.89 PFLOP/s on random operands; both
+// reach 2.46 on constant ones): a 16x16 accumulator block is read and written half as often per FLOP.  Measured
+// in the kernel: +4..6 % where operand A is k-contiguous (forward, data gradients), -3..6 % for the weight
+// gradients at K = 2048, which therefore stay on 32x32x16.
+template <bool TA, bool TB, int WGM, int WGN>
+__device__ __forceinline__ void gemm_mainloop16(f32x4_t (&acc)[kBM / WGM / 16][kBN / WGN / 16], const GemmArgs& g,
+                                              int m0, int n0, int kt0, int kt1, char* smem) {
+  constexpr int NW = WGM * WGN, WM = kBM / WGM, WN = kBN / WGN, RB = WM / 16, CB = WN / 16;
+  static_assert(RB == 8 && CB == 4, "four phases per k-tile: two k32 steps x two halves of the wave's 8 row blocks");
+  constexpr int HB = RB / 2;   // row blocks per phase
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+  // buffer descriptors start at the block's first row so that lane offsets stay small
+  const bf16_t* a_base = TA ? g.A + m0 : g.A + (size_t)m0 * g.lda;
+  const bf16_t* b_base = TB ? g.B + n0 : g.B + (size_t)n0 * g.ldb;
+  const size_t a_left = (size_t)(g.a_end - reinterpret_cast<const char*>(a_base));
+  const size_t b_left = (size_t)(g.b_end - reinterpret_cast<const char*>(b_base));
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, (uint32_t)(a_left < 0x7fffffffu ? a_left : 0x7fffffffu));
+  const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, (uint32_t)(b_left < 0x7fffffffu ? b_left : 0x7fffffffu));
+  const int kend = min(g.K, kt1 * BK);  // k-tiles from kt1 on read as zeros
+
+  TileLoad<TA, NW> la;
+  TileLoad<TB, NW> lb;
+  la.init(g.lda, g.M - m0, wave, lane);
+  lb.init(g.ldb, g.N - n0, wave, lane);
+
+  __syncthreads();  // LDS may still be read by a slower wave of the previous tile
+  la.issue(ra, smem, wave, lane, kt0, kend);
+  lb.issue(rb, smem + kTileBytes, wave, lane, kt0, kend);
+  wait_vmcnt0();
+  __syncthreads();
+
+  // phase p = 2 * ks + half: the MFMAs of row blocks half*4 .. half*4+3 against all four column blocks at k32 step ks
+  bf16x8_t af[2][HB], bfr[2][CB];
+#pragma unroll
+  for (int i = 0; i < HB; ++i) af[0][i] = read_frag16<TA>(smem, wm0 + i * 16, 0, lane);
+#pragma unroll
+  for (int j = 0; j < CB; ++j) bfr[0][j] = read_frag16<TB>(smem + kTileBytes, wn0 + j * 16, 0, lane);
+
+  constexpr bool kIssueBeforeReads = !TA && !TB;
+  auto request = [&](char* stage, int kt) {
+    __builtin_amdgcn_s_setprio(1);
+    la.issue(ra, stage, wave, lane, kt, kend);
+    lb.issue(rb, stage + kTileBytes, wave, lane, kt, kend);
+    __builtin_amdgcn_s_setprio(0);
+  };
+  request(smem + kStageBytes, kt0 + 1);
+  for (int kt = kt0; kt < kt1; ++kt) {
+    char* cur = smem + ((kt - kt0) & 1) * kStageBytes;
+    char* nxt = smem + ((kt - kt0 + 1) & 1) * kStageBytes;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int ks = p >> 1, half = p & 1;
+      if (p < 3) {
+        const int q = p + 1, qs = q >> 1, qh = q & 1;
+#pragma unroll
+        for (int i = 0; i < HB; ++i) af[q & 1][i] = read_frag16<TA>(cur, wm0 + (qh * HB + i) * 16, qs, lane);
+        if (qh == 0) {
+#pragma unroll
+          for (int j = 0; j < CB; ++j) bfr[qs & 1][j] = read_frag16<TB>(cur + kTileBytes, wn0 + j * 16, qs, lane);
+        }
+      } else {
+        // every fragment of `cur` is in registers: the next tile may be consumed, `cur` may be refilled
+        wait_vmcnt0();
+        __syncthreads();
+        // (nothing is requested past the last tile: no load may be in flight when the epilogue reuses LDS)
+        if (kIssueBeforeReads && kt + 2 < kt1) request(cur, kt + 2);
+#pragma unroll
+        for (int i = 0; i < HB; ++i) af[0][i] = read_frag16<TA>(nxt, wm0 + i * 16, 0, lane);
+#pragma unroll
+        for (int j = 0; j < CB; ++j) bfr[0][j] = read_frag16<TB>(nxt + kTileBytes, wn0 + j * 16, 0, lane);
+        if (!kIssueBeforeReads && kt + 2 < kt1) request(cur, kt + 2);
+      }
+#pragma unroll
+      for (int i = 0; i < HB; ++i)
+#pragma unroll
+        for (int j = 0; j < CB; ++j)
+          acc[half * HB + i][j] =
+              __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[p & 1][i], bfr[ks & 1][j], acc[half * HB + i][j], 0, 0, 0);
+      // Scheduling hint: spread this phase's LDS reads between its MFMAs instead of ahead of them
+      if (!TA) {
+#pragma unroll
+        for (int q = 0; q < HB * CB / 2; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+        }
+      }
+    }
+  }
+}
+
+template <int OUT, int WGM, int WGN>
+__device__ __forceinline__ void gemm_epilogue16(const f32x4_t (&acc)[kBM / WGM / 16][kBN / WGN / 16], void* Cv, size_t ldc,
+                                              const bf16_t* bias, int M, int N, int m0, int n0, char* smem) {
+  constexpr int WM = kBM / WGM, WN = kBN / WGN, NS = WM / 32, CB = WN / 16;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+  static_assert(WN == 64, "staging patch is 32 rows x 64 columns per wave");
+  float* patch = reinterpret_cast<float*>(smem) + wave * (32 * kEpiStride);
+  float bv[CB];
+#pragma unroll
+  for (int j = 0; j < CB; ++j) {
+    const int n = n0 + wn0 + j * 16 + (lane & 15);
+    bv[j] = (bias && n < N) ? bf16_to_f32(bias[n]) : 0.f;
+  }
+  const int c4 = (lane & 15) * 4;            // first of this lane's 4 columns inside the wave's 64
+  const int n = n0 + wn0 + c4;
+  // Gradient accumulators are touched once per launch: stream them past the caches.  The old values of
+  // slab i + 1 are requested before slab i is staged and added, so two slabs of loads are in flight.
+  f32x4_t old[2][8];
+  auto fetch_old = [&](int i, f32x4_t (&dst)[8]) {
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int m = m0 + wm0 + i * 32 + it * 4 + (lane >> 4);
+      if (m < M && n < N)
+        dst[it] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n));
+    }
+  };
+  if (OUT == OUT_F32_RMW) fetch_old(0, old[0]);
+#pragma unroll
+  for (int i = 0; i < NS; ++i) {
+    if (OUT == OUT_F32_RMW && i + 1 < NS) fetch_old(i + 1, old[(i + 1) & 1]);
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int j = 0; j < CB; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          patch[(16 * b + 4 * (lane >> 4) + r) * kEpiStride + j * 16 + (lane & 15)] = acc[2 * i + b][j][r] + bv[j];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int row = it * 4 + (lane >> 4);
+      const int m = m0 + wm0 + i * 32 + row;
+      const float4 v = *reinterpret_cast<const float4*>(patch + row * kEpiStride + c4);
+      if (m < M && n < N) {
+        if (OUT == OUT_BF16) {
+          uint2 o;
+          o.x = pack_bf16x2(v.x, v.y);
+          o.y = pack_bf16x2(v.z, v.w);
+          *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(Cv) + (size_t)m * ldc + n) = o;
+        } else if (OUT == OUT_F32_RMW) {
+          f32x4_t o = old[i & 1][it];
+          o[0] += v.x; o[1] += v.y; o[2] += v.z; o[3] += v.w;
+          __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n));
+        } else {
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(Cv) + (size_t)m * ldc + n) = v;
+        }
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+template <int TM, int TN> __device__ __forceinline__ void zero_acc(f32x4_t (&acc)[TM][TN]) {
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+}
+
+// One 256 x 256 tile over k-tiles kt0 .. kt1-1, written either in the caller's output form (slab == nullptr) or
+// as a dense 256 x 256 fp32 slab.  The MFMA shape follows operand A's layout (see above).
+template <bool TA, bool TB, int OUT, int WGM, int WGN>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, void* Cv, float* slab, int m0, int n0, int kt0, int kt1, char* smem) {
+  if constexpr (TA) {
+    f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
+    zero_acc(acc);
+    if (kt1 > kt0) gemm_mainloop<TA, TB, WGM, WGN>(acc, g, m0, n0, kt0, kt1, smem);
+    if (slab) gemm_epilogue<OUT_F32_STORE, WGM, WGN>(acc, slab, kBN, nullptr, kBM, kBN, 0, 0, smem);
+    else gemm_epilogue<OUT, WGM, WGN>(acc, Cv, g.ldc, g.bias, g.M, g.N, m0, n0, smem);
+  } else {
+    f32x4_t acc[kBM / WGM / 16][kBN / WGN / 16];
+    zero_acc(acc);
+    if (kt1 > kt0) gemm_mainloop16<TA, TB, WGM, WGN>(acc, g, m0, n0, kt0, kt1, smem);
+    if (slab) gemm_epilogue16<OUT_F32_STORE, WGM, WGN>(acc, slab, kBN, nullptr, kBM, kBN, 0, 0, smem);
+    else gemm_epilogue16<OUT, WGM, WGN>(acc, Cv, g.ldc, g.bias, g.M, g.N, m0, n0, smem);
+  }
+}
+
 // One workgroup per output tile ("data-parallel" form); `id` is the workgroup's index inside its problem.
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Each XCD owns the column
 // tiles x, x+8, ... and works through them in groups of up to 8 row tiles, so that the
@@ -359,10 +566,7 @@ __device__ __forceinline__ void gemm_dp_tile(const GemmArgs& g, void* Cv, int id
   const int gm = min(8, tiles_m - grp * 8);         // row tiles in this group
   const int tile_m = grp * 8 + in_grp % gm, tile_n = (in_grp / gm) * 8 + xcd;
   if (tile_n >= tiles_n) return;
-  f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
-  zero_acc(acc);
-  gemm_mainloop<TA, TB, WGM, WGN>(acc, g, tile_m * kBM, tile_n * kBN, 0, (g.K + BK - 1) / BK, smem);
-  gemm_epilogue<OUT, WGM, WGN>(acc, Cv, g.ldc, g.bias, g.M, g.N, tile_m * kBM, tile_n * kBN, smem);
+  gemm_tile<TA, TB, OUT, WGM, WGN>(g, Cv, nullptr, tile_m * kBM, tile_n * kBN, 0, (g.K + BK - 1) / BK, smem);
 }
 // workgroups of one problem (a multiple of 8, so that a second problem starts on XCD 0 again)
 static inline int dp_blocks(const GemmArgs& g) {
@@ -430,14 +634,8 @@ gemm_bf16_split_kernel(GemmArgs g, void* Cv, float* slabs, SplitGroups sg) {
   const int m0 = (tile % tiles_m) * kBM, n0 = (tile / tiles_m) * kBN;
   const int nk = (g.K + BK - 1) / BK;
   const int kt0 = (int)((long long)nk * part / parts), kt1 = (int)((long long)nk * (part + 1) / parts);
-  f32x16_t acc[kBM / WGM / 32][kBN / WGN / 32];
-  zero_acc(acc);
-  if (kt1 > kt0) gemm_mainloop<TA, TB, WGM, WGN>(acc, g, m0, n0, kt0, kt1, smem);
-  if (parts == 1)
-    gemm_epilogue<OUT, WGM, WGN>(acc, Cv, g.ldc, g.bias, g.M, g.N, m0, n0, smem);
-  else
-    gemm_epilogue<OUT_F32_STORE, WGM, WGN>(acc, slabs + (size_t)(sg.slab0[j] + unit) * kSlabFloats, kBN, nullptr, kBM, kBN, 0, 0,
-                                           smem);
+  gemm_tile<TA, TB, OUT, WGM, WGN>(g, Cv, parts == 1 ? nullptr : slabs + (size_t)(sg.slab0[j] + unit) * kSlabFloats, m0, n0, kt0, kt1,
+                                   smem);
 }
 
 // One workgroup per (tile of a split group, 16-row band): sums the tile's slabs in part order and writes
