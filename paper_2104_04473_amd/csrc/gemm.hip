@@ -297,6 +297,7 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kB
 //     row segment: 16-byte fp32 or 8-byte bf16 accesses instead of scalar ones.
 enum { OUT_BF16 = 0, OUT_F32_STORE = 1, OUT_F32_RMW = 2 };
 constexpr int kEpiStride = 72;  // floats per staged row of 64: rows 4 apart land 32 banks apart
+constexpr int kEpiStride16 = 68;  // 16x16 blocks: a store covers rows 0, 4, 8, 12 of a block, which land 16 banks apart
 
 template <int OUT, int WGM, int WGN>
 __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[kBM / WGM / 32][kBN / WGN / 32], void* Cv, size_t ldc,
@@ -468,7 +469,7 @@ __device__ __forceinline__ void gemm_epilogue16(const f32x4_t (&acc)[kBM / WGM /
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
   static_assert(WN == 64, "staging patch is 32 rows x 64 columns per wave");
-  float* patch = reinterpret_cast<float*>(smem) + wave * (32 * kEpiStride);
+  float* patch = reinterpret_cast<float*>(smem) + wave * (32 * kEpiStride16);
   float bv[CB];
 #pragma unroll
   for (int j = 0; j < CB; ++j) {
@@ -498,13 +499,13 @@ __device__ __forceinline__ void gemm_epilogue16(const f32x4_t (&acc)[kBM / WGM /
       for (int j = 0; j < CB; ++j)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-          patch[(16 * b + 4 * (lane >> 4) + r) * kEpiStride + j * 16 + (lane & 15)] = acc[2 * i + b][j][r] + bv[j];
+          patch[(16 * b + 4 * (lane >> 4) + r) * kEpiStride16 + j * 16 + (lane & 15)] = acc[2 * i + b][j][r] + bv[j];
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       const int row = it * 4 + (lane >> 4);
       const int m = m0 + wm0 + i * 32 + row;
-      const float4 v = *reinterpret_cast<const float4*>(patch + row * kEpiStride + c4);
+      const float4 v = *reinterpret_cast<const float4*>(patch + row * kEpiStride16 + c4);
       if (m < M && n < N) {
         if (OUT == OUT_BF16) {
           uint2 o;
