@@ -76,7 +76,8 @@ gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B, float*
 //   k-contiguous operand: [row][BKT/8 chunks of 16 B]; chunk c of row r sits in slot c ^ f(r), f chosen
 //     so that 16 neighbouring rows of one fragment read fall into 16 different 16-byte bank groups.
 //   k-slow operand (memory [k][row]): [k][32 chunks of 16 B] (512 B per k); chunk c of k-row k sits in
-//     slot c ^ (4 * (k & 3)).  MFMA fragments are gathered with ds_read_b64_tr_b16: within 16 lanes,
+//     slot c ^ (4 * (k & 3)) ^ (2 * ((k >> 3) & 1)): the four k-rows that one group of 16 lanes gathers land in
+//     different bank groups, and so do k-rows 8 apart, which the 16x16x32 fragments read in the same cycle.  MFMA fragments are gathered with ds_read_b64_tr_b16: within 16 lanes,
 //     lane i receives element (i & 3) of the 8-byte rows addressed by lanes (i >> 2) + {0, 4, 8, 12}.
 // ------------------------------------------------------------------------------------------------
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
@@ -113,7 +114,7 @@ template <bool KSLOW, int NW> struct TileLoad {
         off[i] = row < rows_left ? (uint32_t)(((size_t)row * ld + chunk * 8) * 2) : kOob;
       } else {
         const int k = li * 2 + (lane >> 5);
-        const int chunk = (lane & 31) ^ (4 * (k & 3));
+        const int chunk = (lane & 31) ^ (4 * (k & 3)) ^ (2 * ((k >> 3) & 1));
         off[i] = chunk * 8 < rows_left ? (uint32_t)(((size_t)k * ld + chunk * 8) * 2) : kOob;
       }
     }
@@ -146,8 +147,8 @@ __device__ __forceinline__ bf16x8_t read_frag(const char* tile, int row_base, in
   } else {
     const int r = lane & 15, G = lane >> 4;
     const int n0 = row_base + 16 * (G & 1) + 4 * (r & 3);
-    const int k = kk * 16 + 8 * (G >> 1) + (r >> 2);  // (k & 3) == r >> 2 for both halves
-    const int slot = (n0 >> 3) ^ (4 * (r >> 2));
+    const int k = kk * 16 + 8 * (G >> 1) + (r >> 2);  // (k & 3) == r >> 2 and (k >> 3) & 1 == G >> 1 for both halves
+    const int slot = (n0 >> 3) ^ (4 * (r >> 2)) ^ (2 * (G >> 1));
     const char* p = tile + k * 512 + slot * 16 + (n0 & 7) * 2;
     const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
     const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p + 4 * 512));
@@ -169,8 +170,8 @@ __device__ __forceinline__ bf16x8_t read_frag16(const char* tile, int row_base, 
   } else {
     const int r = lane & 15, G = lane >> 4;
     const int n0 = row_base + 4 * (r & 3);
-    const int k = ks * 32 + 8 * G + (r >> 2);  // (k & 3) == r >> 2 for both halves
-    const int slot = (n0 >> 3) ^ (4 * (r >> 2));
+    const int k = ks * 32 + 8 * G + (r >> 2);  // (k & 3) == r >> 2 and (k >> 3) & 1 == G & 1 for both halves
+    const int slot = (n0 >> 3) ^ (4 * (r >> 2)) ^ (2 * (G & 1));
     const char* p = tile + k * 512 + slot * 16 + (n0 & 7) * 2;
     const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p));
     const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t __attribute__((address_space(3)))*)(p + 4 * 512));
