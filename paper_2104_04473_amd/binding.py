@@ -12,7 +12,8 @@ import os
 import torch  # noqa: F401  (device memory and streams only)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libptdp.so")
+# PTDP_LIB names another build of the same library (e.g. the host-sanitizer build of `build.py --sanitize`)
+LIB_PATH = os.environ.get("PTDP_LIB") or os.path.join(_HERE, "libptdp.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(

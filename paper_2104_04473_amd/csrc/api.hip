@@ -2,6 +2,7 @@
 // pipeline order of one device, profiling.  Every exported function is declared in include/ptdp.h.
 #include <new>
 #include <cmath>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -14,7 +15,8 @@ struct ProfRecord {
   double work;
   hipEvent_t start, stop;
 };
-static bool g_prof_on = false;
+static std::atomic<bool> g_prof_on{false};
+static std::mutex g_prof_mu;                // guards the three containers below
 static std::vector<ProfRecord> g_open;      // recorded, not yet collected
 static std::vector<hipEvent_t> g_free_events;
 static ptdp_prof_entry g_totals[PTDP_K_NFAMILIES];
@@ -28,11 +30,12 @@ static bool get_event(hipEvent_t* e) {
   return hipEventCreate(e) == hipSuccess;
 }
 
-bool profiling_enabled() { return g_prof_on; }
+bool profiling_enabled() { return g_prof_on.load(std::memory_order_relaxed); }
 
 Launch::Launch(int family, double work, hipStream_t stream) : stream_(stream), slot_(-1), status_(PTDP_OK), closed_(false) {
   (void)hipGetLastError();  // do not inherit a stale error
-  if (!g_prof_on) return;
+  if (!g_prof_on.load(std::memory_order_relaxed)) return;
+  std::lock_guard<std::mutex> lock(g_prof_mu);
   ProfRecord r;
   r.family = family;
   r.work = work;
@@ -47,7 +50,11 @@ int Launch::status() {
   if (!closed_) {
     closed_ = true;
     if (hipGetLastError() != hipSuccess) status_ = PTDP_E_HIP;
-    if (slot_ >= 0 && hipEventRecord(g_open[slot_].stop, stream_) != hipSuccess) status_ = PTDP_E_HIP;
+    if (slot_ >= 0) {
+      std::lock_guard<std::mutex> lock(g_prof_mu);
+      // (a collect between the two halves of a launch has already retired the record: nothing to stop)
+      if (slot_ < (int)g_open.size() && hipEventRecord(g_open[slot_].stop, stream_) != hipSuccess) status_ = PTDP_E_HIP;
+    }
   }
   return status_;
 }
@@ -880,6 +887,7 @@ int ptdp_attn_masked_bwd(int dtype, const void* qkv, const uint8_t* mask, const 
 
 // ----------------------------------------------------------------------------------- profiling
 int ptdp_prof_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_prof_mu);
   if (on) {
     for (int i = 0; i < PTDP_K_NFAMILIES; ++i) g_totals[i] = ptdp_prof_entry{0.0, 0.0, 0};
     for (auto& r : g_open) {
@@ -888,12 +896,13 @@ int ptdp_prof_enable(int on) {
     }
     g_open.clear();
   }
-  g_prof_on = on != 0;
+  g_prof_on.store(on != 0, std::memory_order_relaxed);
   return PTDP_OK;
 }
 
 int ptdp_prof_collect(ptdp_prof_entry* out) {
   if (!out) return PTDP_E_NULL_PTR;
+  std::lock_guard<std::mutex> lock(g_prof_mu);
   int rc = PTDP_OK;
   for (auto& r : g_open) {
     float ms = 0.f;

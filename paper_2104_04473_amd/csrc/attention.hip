@@ -804,7 +804,7 @@ template <int DH, bool CAUSAL>
 static int attn_fwd_mfma_t(const bf16_t* qkv, bf16_t* ctx, float* lse, int s, int b, int heads, const uint8_t* mask,
                            hipStream_t stream) {
   constexpr int smem = 2 * TileGeom<DH>::BYTES;
-  static bool done[kMaxDevices] = {};
+  static once_flag_t done[kMaxDevices];
   if (set_dynamic_smem(reinterpret_cast<const void*>(attn_fwd_mfma<DH, CAUSAL>), smem, done) != PTDP_OK) return PTDP_E_HIP;
   const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
   hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL>), grid, dim3(kAttnThreads), smem, stream, qkv, ctx, lse, s, b, heads, mask);
@@ -857,7 +857,7 @@ static int attn_bwd_mfma_t(const bf16_t* qkv, const bf16_t* ctx, const float* ls
                            float* delta, int s, int b, int heads, const uint8_t* mask, hipStream_t stream) {
   constexpr int smem_dq = 2 * TileGeom<DH>::BYTES;
   constexpr int smem_dkv = 2 * TileGeom<DH>::BYTES + 2 * kBKV * (int)sizeof(float) + (CAUSAL ? 0 : kBQ * kMaskLdsStride);
-  static bool done_dq[kMaxDevices] = {}, done_dkv[kMaxDevices] = {};
+  static once_flag_t done_dq[kMaxDevices], done_dkv[kMaxDevices];
   if (set_dynamic_smem(reinterpret_cast<const void*>(attn_bwd_dq_mfma<DH, CAUSAL>), smem_dq, done_dq) != PTDP_OK ||
       set_dynamic_smem(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH, CAUSAL>), smem_dkv, done_dkv) != PTDP_OK)
     return PTDP_E_HIP;

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "ptdp.h"
 
 namespace ptdp {
@@ -117,12 +119,14 @@ inline int device_slot() {
   int d = 0;
   return (hipGetDevice(&d) == hipSuccess && d >= 0 && d < kMaxDevices) ? d : -1;
 }
-// Raises a kernel's dynamic shared memory limit once per device; `done` is that kernel's flag array.
-inline int set_dynamic_smem(const void* kern, int bytes, bool (&done)[kMaxDevices]) {
+// Raises a kernel's dynamic shared memory limit once per device; `done` is that kernel's flag array.  Threads
+// that race here both make the (idempotent) call; the flags are atomics so that the race is a defined one.
+typedef std::atomic<bool> once_flag_t;
+inline int set_dynamic_smem(const void* kern, int bytes, once_flag_t (&done)[kMaxDevices]) {
   const int d = device_slot();
-  if (d >= 0 && done[d]) return PTDP_OK;
+  if (d >= 0 && done[d].load(std::memory_order_acquire)) return PTDP_OK;
   if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return PTDP_E_HIP;
-  if (d >= 0) done[d] = true;
+  if (d >= 0) done[d].store(true, std::memory_order_release);
   return PTDP_OK;
 }
 

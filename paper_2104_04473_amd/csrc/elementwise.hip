@@ -610,17 +610,17 @@ int launch_bda_bwd(int dtype, const void* dout, void* din, float* dbias, void* s
 // ends.  In host code `scratch` is only a handle for hipGetSymbolAddress, never a device address: every
 // launch below is handed the address looked up once per device, with that device current.
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
-static void* g_scratch_ptr[kMaxDevices] = {};
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
 
 static int static_scratch(void** out) {
   const int d = device_slot();
   if (d < 0) return PTDP_E_HIP;
-  if (!g_scratch_ptr[d]) {
-    void* ptr = nullptr;
+  void* ptr = g_scratch_ptr[d].load(std::memory_order_acquire);
+  if (!ptr) {
     if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return PTDP_E_HIP;
-    g_scratch_ptr[d] = ptr;
+    g_scratch_ptr[d].store(ptr, std::memory_order_release);   // racing threads store the same address
   }
-  *out = g_scratch_ptr[d];
+  *out = ptr;
   return PTDP_OK;
 }
 

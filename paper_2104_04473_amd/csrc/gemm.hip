@@ -694,7 +694,7 @@ constexpr int kWGM = 2, kWGN = 4, kGemmThreads = kWGM * kWGN * 64, kGemmSmem = 2
 template <bool TA, bool TB, int OUT>
 static int launch_dp(const GemmArgs& g, void* C, hipStream_t st) {
   auto kern = gemm_bf16_dp_kernel<TA, TB, OUT, kWGM, kWGN>;
-  static bool done[kMaxDevices] = {};
+  static once_flag_t done[kMaxDevices];
   if (set_dynamic_smem(reinterpret_cast<const void*>(kern), kGemmSmem, done) != PTDP_OK) return PTDP_E_HIP;
   hipLaunchKernelGGL(kern, dim3(dp_blocks(g)), dim3(kGemmThreads), kGemmSmem, st, g, C);
   return PTDP_OK;
@@ -703,21 +703,21 @@ static int launch_dp(const GemmArgs& g, void* C, hipStream_t st) {
 template <bool TA, bool TB, int OUT>
 static int launch_split(const GemmArgs& g, void* C, float* slabs, const SplitGroups& sg, int blocks, hipStream_t st) {
   auto kern = gemm_bf16_split_kernel<TA, TB, OUT, kWGM, kWGN>;
-  static bool done[kMaxDevices] = {};
+  static once_flag_t done[kMaxDevices];
   if (set_dynamic_smem(reinterpret_cast<const void*>(kern), kGemmSmem, done) != PTDP_OK) return PTDP_E_HIP;
   hipLaunchKernelGGL(kern, dim3(blocks), dim3(kGemmThreads), kGemmSmem, st, g, C, slabs, sg);
   return PTDP_OK;
 }
 
 static int compute_units() {
-  static int n[kMaxDevices] = {};
+  static std::atomic<int> n[kMaxDevices];
   const int d = device_slot();
-  if (d >= 0 && n[d] > 0) return n[d];
+  if (d >= 0 && n[d].load(std::memory_order_relaxed) > 0) return n[d].load(std::memory_order_relaxed);
   hipDeviceProp_t prop;
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 256;
   const int cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  if (d >= 0) n[d] = cu;
+  if (d >= 0) n[d].store(cu, std::memory_order_relaxed);
   return cu;
 }
 
@@ -896,7 +896,7 @@ int launch_gemm_tn_pair(int dtype, const void* A0, const void* B0, float* C0, in
   Launch L(PTDP_K_GEMM_TN, 2.0 * K * ((double)M0 * N0 + (double)M1 * N1), st);
   const GemmArgs g0 = tn_args(A0, B0, M0, N0, K), g1 = tn_args(A1, B1, M1, N1, K);
   auto kern = gemm_bf16_dp_pair_kernel<true, true, OUT_F32_RMW, kWGM, kWGN>;
-  static bool done[kMaxDevices] = {};
+  static once_flag_t done[kMaxDevices];
   if (set_dynamic_smem(reinterpret_cast<const void*>(kern), kGemmSmem, done) != PTDP_OK) return PTDP_E_HIP;
   const int n0 = dp_blocks(g0);
   hipLaunchKernelGGL(kern, dim3(n0 + dp_blocks(g1)), dim3(kGemmThreads), kGemmSmem, st, g0, (void*)C0, g1, (void*)C1, n0);
