@@ -230,7 +230,10 @@ def main():
     traffic = measured_traffic(args.workload, dom)
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(dwork / (dms * 1e-3) / 1e12, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(dwork / (dms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                "traffic": traffic, "flops_per_launch": dwork / dl, "avg_launch_ms": round(dms / dl, 5),
+                "traffic": traffic,
+                "traffic_source": None if traffic is None else "profiles/%s_hbm_traffic.txt: rocprofv3 FETCH_SIZE + WRITE_SIZE per "
+                                  "library launch of this family, two separate counter runs of this script (not this run)" % args.workload,
+                "flops_per_launch": dwork / dl, "avg_launch_ms": round(dms / dl, 5),
                 "all_gemm_achieved": round(all_work / (all_ms * 1e-3) / 1e12, 2),
                 "all_gemm_share_of_step": round(all_ms / prof_steps / ms_per_step, 4)}
 
@@ -249,10 +252,12 @@ def main():
     fl = C.c_double(0.0)
     t_m = timed(lambda: B.check(B.ptdp_ceiling_mfma(sink.data_ptr(), 256 * 4, 20000, 0, C.byref(fl), sh), "ceiling_mfma"), 3)
     t_r = timed(lambda: B.check(B.ptdp_ceiling_mfma(sink.data_ptr(), 256 * 4, 20000, 1, C.byref(fl), sh), "ceiling_mfma"), 3)
+    t_r16 = timed(lambda: B.check(B.ptdp_ceiling_mfma(sink.data_ptr(), 256 * 4, 20000, 3, C.byref(fl), sh), "ceiling_mfma"), 3)
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev); dst = torch.empty_like(src)
     t_c = timed(lambda: B.check(B.ptdp_ceiling_copy(src.data_ptr(), dst.data_ptr(), src.numel(), sh), "ceiling_copy"), 5)
     ceilings = {"mfma_bf16_register_loop_tflops": round(fl.value / t_m / 1e12, 1),
                 "mfma_bf16_register_loop_random_operands_tflops": round(fl.value / t_r / 1e12, 1),
+                "mfma_bf16_16x16x32_register_loop_random_operands_tflops": round(fl.value / t_r16 / 1e12, 1),
                 "copy_1gib_read_plus_write_gbs": round(2 * src.numel() / t_c / 1e9, 1)}
     del src, dst
 

@@ -435,7 +435,9 @@ int ptdp_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse,
  * v_mfma_f32_32x32x16_bf16 on registers only (workgroups x 8 waves x 8
  * accumulators x iters instructions; random_operands 0: small constant
  * integers, 1: hash-derived values spread like N(0,1), rotated between
- * instructions as in a GEMM (more toggling bits, lower sustained clock);
+ * instructions as in a GEMM (more toggling bits, lower sustained clock); +2:
+ * the same loop on v_mfma_f32_16x16x32_bf16, the shape of the forward and
+ * data-gradient GEMMs);
  * *flops (host) receives the FLOP count of the launch; sink: dev, >= 4 bytes,
  * not written in practice), and a copy of
  * `bytes` (multiple of 16, 16-byte aligned pointers) with 16 bytes per lane.
