@@ -213,7 +213,7 @@ template <bool TA, bool TB, int WGM, int WGN>
 __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kBN / WGN / 32], const GemmArgs& g,
                                               int m0, int n0, int kt0, int kt1, char* smem) {
   constexpr int NW = WGM * WGN, WM = kBM / WGM, WN = kBN / WGN, TM = WM / 32, TN = WN / 32, NKK = BK / 16;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave-uniform: LDS bases and M0 values stay in scalar registers
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
   // buffer descriptors start at the block's first row so that lane offsets stay small
   const bf16_t* a_base = TA ? g.A + m0 : g.A + (size_t)m0 * g.lda;
@@ -304,7 +304,7 @@ template <int OUT, int WGM, int WGN>
 __device__ __forceinline__ void gemm_epilogue(const f32x16_t (&acc)[kBM / WGM / 32][kBN / WGN / 32], void* Cv, size_t ldc,
                                               const bf16_t* bias, int M, int N, int m0, int n0, char* smem) {
   constexpr int WM = kBM / WGM, WN = kBN / WGN, TM = WM / 32, TN = WN / 32;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave-uniform: LDS bases and M0 values stay in scalar registers
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
   static_assert(WN == 64, "staging patch is 32 rows x 64 columns per wave");
   float* patch = reinterpret_cast<float*>(smem) + wave * (32 * kEpiStride);
@@ -382,7 +382,7 @@ __device__ __forceinline__ void gemm_mainloop16(f32x4_t (&acc)[kBM / WGM / 16][k
   constexpr int NW = WGM * WGN, WM = kBM / WGM, WN = kBN / WGN, RB = WM / 16, CB = WN / 16;
   static_assert(RB == 8 && CB == 4, "four phases per k-tile: two k32 steps x two halves of the wave's 8 row blocks");
   constexpr int HB = RB / 2;   // row blocks per phase
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave-uniform: LDS bases and M0 values stay in scalar registers
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
   // buffer descriptors start at the block's first row so that lane offsets stay small
   const bf16_t* a_base = TA ? g.A + m0 : g.A + (size_t)m0 * g.lda;
@@ -467,7 +467,7 @@ template <int OUT, int WGM, int WGN>
 __device__ __forceinline__ void gemm_epilogue16(const f32x4_t (&acc)[kBM / WGM / 16][kBN / WGN / 16], void* Cv, size_t ldc,
                                               const bf16_t* bias, int M, int N, int m0, int n0, char* smem) {
   constexpr int WM = kBM / WGM, WN = kBN / WGN, NS = WM / 32, CB = WN / 16;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave-uniform: LDS bases and M0 values stay in scalar registers
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
   static_assert(WN == 64, "staging patch is 32 rows x 64 columns per wave");
   float* patch = reinterpret_cast<float*>(smem) + wave * (32 * kEpiStride16);
