@@ -149,6 +149,7 @@ enum {
   PTDP_WS_DZ,      /* grad of (z + b_1)                                [T, fp]  */
   PTDP_WS_DCTX,    /* grad of the attention output                     [T, hp]  */
   PTDP_WS_DQKV,    /* grad of Q|K|V                                    [T, 3hp] */
+  PTDP_WS_DMO,     /* grad of (mo + b_2) = dy * mask_1 / (1-p)         [T, h]   */
   PTDP_WS_NFIELDS
 };
 /* Byte offset of such a field in the workspace; (size_t)-1 on an invalid cfg or field. */

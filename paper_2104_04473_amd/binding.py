@@ -26,7 +26,7 @@ F32, BF16 = 0, 1
 GELU_ERF, GELU_TANH = 0, 1
 GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 STASH_FIELDS = ("X", "U", "QKV", "CTX", "X1", "U2", "Z", "G", "MU1", "RSTD1", "MU2", "RSTD2", "LSE")
-WS_FIELDS = ("DO", "DU", "DX1", "CHAIN", "DZ", "DCTX", "DQKV")
+WS_FIELDS = ("DO", "DU", "DX1", "CHAIN", "DZ", "DCTX", "DQKV", "DMO")
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
 PROF_FAMILIES = 15
 

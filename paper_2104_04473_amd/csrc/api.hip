@@ -136,7 +136,7 @@ static StashLayout stash_layout(const ptdp_layer_cfg* c) {
 }
 
 // workspace fields
-enum { WS_H1 = 0, WS_H2, WS_X1, WS_CHAIN, WS_BIG, WS_CTX, WS_QKV, WS_DELTA, WS_COLSUM, WS_SPLITK, WS_N };
+enum { WS_H1 = 0, WS_H2, WS_X1, WS_CHAIN, WS_BIG, WS_CTX, WS_QKV, WS_DMO, WS_DELTA, WS_COLSUM, WS_SPLITK, WS_N };
 struct WsLayout {
   size_t off[WS_N];
   size_t total;
@@ -144,7 +144,7 @@ struct WsLayout {
 static WsLayout ws_layout(const ptdp_layer_cfg* c) {
   const Dims d = dims_of(c);
   size_t sz[WS_N];
-  sz[WS_H1] = sz[WS_H2] = sz[WS_X1] = sz[WS_CHAIN] = d.T * d.h * d.esz;
+  sz[WS_H1] = sz[WS_H2] = sz[WS_X1] = sz[WS_CHAIN] = sz[WS_DMO] = d.T * d.h * d.esz;
   sz[WS_BIG] = d.T * d.fp * d.esz;
   sz[WS_CTX] = d.T * d.hp * d.esz;
   sz[WS_QKV] = d.T * 3 * d.hp * d.esz;
@@ -222,7 +222,7 @@ size_t ptdp_workspace_bytes(const ptdp_layer_cfg* cfg) {
 
 size_t ptdp_workspace_offset(const ptdp_layer_cfg* cfg, int field) {
   static_assert(PTDP_WS_DO == WS_H1 && PTDP_WS_DU == WS_H2 && PTDP_WS_DX1 == WS_X1 && PTDP_WS_CHAIN == WS_CHAIN &&
-                    PTDP_WS_DZ == WS_BIG && PTDP_WS_DCTX == WS_CTX && PTDP_WS_DQKV == WS_QKV,
+                    PTDP_WS_DZ == WS_BIG && PTDP_WS_DCTX == WS_CTX && PTDP_WS_DQKV == WS_QKV && PTDP_WS_DMO == WS_DMO,
                 "public workspace fields are the first internal ones, in order");
   if (validate(cfg) != PTDP_OK || field < 0 || field >= PTDP_WS_NFIELDS) return (size_t)-1;
   return ws_layout(cfg).off[field];
@@ -366,29 +366,31 @@ int ptdp_layer_backward(ptdp_chunk* ch, int layer, int64_t microbatch, const voi
   void* sk = wf(WS_SPLITK);
   const size_t skb = ws_field_bytes(ch->wl, WS_SPLITK);
 
-  // MLP block
-  PTDP_TRY(launch_bda_bwd(dt, dy, wf(WS_H1), G.b_2, cs, T, h, c.p_hidden,
+  // MLP block.  The four weight gradients of the layer wait until all their inputs are there and run as one
+  // launch at the end (each one's tiles fill the last, partial round of the ones before it); until then G, U2,
+  // CTX, U and the gradients d(mo) [WS_DMO], dz [WS_BIG], do [WS_H1], dqkv [WS_QKV] stay untouched.
+  PTDP_TRY(launch_bda_bwd(dt, dy, wf(WS_DMO), G.b_2, cs, T, h, c.p_hidden,
                           dropout_key(c.seed, gl, 1, (uint64_t)microbatch), st));
-  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_2, wf(WS_BIG), nullptr, T, fp, h, 0, 0, sk, skb, st));
-  // (the weight gradient of w_2 waits for that of w_1: the two run as one launch, so that the second one's
-  // tiles fill the last, partial round of the first; its inputs G and WS_H1 stay untouched until then)
+  PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_DMO), P.w_2, wf(WS_BIG), nullptr, T, fp, h, 0, 0, sk, skb, st));
   PTDP_TRY(launch_bias_gelu_bwd(dt, c.gelu_mode, wf(WS_BIG), sf(PTDP_STASH_Z), P.b_1, wf(WS_BIG), G.b_1, cs, T, fp, st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_BIG), P.w_1, wf(WS_H2), nullptr, T, h, fp, 0, 0, sk, skb, st));
-  PTDP_TRY(launch_gemm_tn_pair(dt, sf(PTDP_STASH_G), wf(WS_H1), G.w_2, fp, h, sf(PTDP_STASH_U2), wf(WS_BIG), G.w_1, h, fp,
-                               T, st));
   PTDP_TRY(launch_layernorm_bwd(dt, wf(WS_H2), sf(PTDP_STASH_X1), P.ln2_g, (const float*)sf(PTDP_STASH_MU2),
                                 (const float*)sf(PTDP_STASH_RSTD2), dy, wf(WS_X1), G.ln2_g, G.ln2_b, cs, T, h, st));
   // attention block
   PTDP_TRY(launch_bda_bwd(dt, wf(WS_X1), wf(WS_H1), G.b_o, cs, T, h, c.p_hidden,
                           dropout_key(c.seed, gl, 0, (uint64_t)microbatch), st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_o, wf(WS_CTX), nullptr, T, hp, h, 0, 0, sk, skb, st));
-  // (w_o's weight gradient runs paired with w_qkv's below; CTX and WS_H1 stay untouched until then)
   PTDP_TRY(launch_attn_bwd(dt, sf(PTDP_STASH_QKV), sf(PTDP_STASH_CTX), (const float*)sf(PTDP_STASH_LSE), wf(WS_CTX),
                            wf(WS_QKV), (float*)wf(WS_DELTA), c.s, c.b, (int)d.al, (int)d.dh, ch->mask, c.causal, st));
   PTDP_TRY(launch_colsum(dt, wf(WS_QKV), G.b_qkv, cs, T, 3 * hp, st));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_QKV), P.w_qkv, wf(WS_H2), nullptr, T, h, 3 * hp, 0, 0, sk, skb, st));
-  PTDP_TRY(launch_gemm_tn_pair(dt, sf(PTDP_STASH_U), wf(WS_QKV), G.w_qkv, h, 3 * hp, sf(PTDP_STASH_CTX), wf(WS_H1), G.w_o, hp,
-                               h, T, st));
+  {
+    const void* A[4] = {sf(PTDP_STASH_G), sf(PTDP_STASH_U2), sf(PTDP_STASH_U), sf(PTDP_STASH_CTX)};
+    const void* B[4] = {wf(WS_DMO), wf(WS_BIG), wf(WS_QKV), wf(WS_H1)};
+    float* C[4] = {G.w_2, G.w_1, G.w_qkv, G.w_o};
+    const int M[4] = {fp, h, h, hp}, N[4] = {h, fp, 3 * hp, h};
+    PTDP_TRY(launch_gemm_tn_multi(dt, 4, A, B, C, M, N, T, st));
+  }
   PTDP_TRY(launch_layernorm_bwd(dt, wf(WS_H2), sf(PTDP_STASH_X), P.ln1_g, (const float*)sf(PTDP_STASH_MU1),
                                 (const float*)sf(PTDP_STASH_RSTD1), wf(WS_X1), dx, G.ln1_g, G.ln1_b, cs, T, h, st));
   return PTDP_OK;

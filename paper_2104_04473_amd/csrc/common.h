@@ -162,9 +162,9 @@ void gemm_plan_query(int M, int N, int K, int out_f32, int accumulate, int has_b
                      int* n_groups, int* tiles, int* parts);
 int launch_gemm(int dtype, int mode, const void* A, const void* B, void* C, const void* bias, int M, int N,
                 int K, int out_f32, int accumulate, void* ws, size_t ws_bytes, hipStream_t st);
-// two fp32-accumulating weight gradients C += A^T B with the same K (bf16: one launch)
-int launch_gemm_tn_pair(int dtype, const void* A0, const void* B0, float* C0, int M0, int N0, const void* A1,
-                        const void* B1, float* C1, int M1, int N1, int K, hipStream_t st);
+// up to four fp32-accumulating weight gradients C_j += A_j^T B_j with the same K (bf16: one launch)
+int launch_gemm_tn_multi(int dtype, int n, const void* const* A, const void* const* B, float* const* C, const int* M,
+                         const int* N, int K, hipStream_t st);
 // mask: [b, s, s] bytes (nonzero = hidden) or null, used when causal == 0
 int launch_attn_fwd(int dtype, const void* qkv, void* ctx, float* lse, int s, int b, int heads, int dh,
                     const uint8_t* mask, int causal, hipStream_t st);

@@ -651,14 +651,33 @@ gemm_bf16_dp_kernel(GemmArgs g, void* Cv) {
   gemm_dp_tile<TA, TB, OUT, WGM, WGN>(g, Cv, blockIdx.x, smem);
 }
 
-// Two independent problems of the same form in one launch: the second one's workgroups fill the CUs that
-// the first one's last, partial round of tiles would leave idle.  n0 = dp_blocks(g0).
+// Up to four independent problems of the same form in one launch: each later problem's tiles fill the CUs that the
+// last, partial round of the ones before it would leave idle.  start[j] = first workgroup index of problem j
+// (multiples of 8, so that every problem starts on XCD 0), start[n] = grid size.
+constexpr int kMaxMulti = 4;
+struct MultiArgs {
+  GemmArgs g[kMaxMulti];
+  void* C[kMaxMulti];
+  int start[kMaxMulti + 1];
+  int n;
+};
 template <bool TA, bool TB, int OUT, int WGM, int WGN>
 __global__ void __launch_bounds__(WGM * WGN * 64)
-gemm_bf16_dp_pair_kernel(GemmArgs g0, void* C0, GemmArgs g1, void* C1, int n0) {
+gemm_bf16_dp_multi_kernel(MultiArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  if ((int)blockIdx.x < n0) gemm_dp_tile<TA, TB, OUT, WGM, WGN>(g0, C0, blockIdx.x, smem);
-  else gemm_dp_tile<TA, TB, OUT, WGM, WGN>(g1, C1, blockIdx.x - n0, smem);
+  const int id = (int)blockIdx.x;
+  // constant indices only: the arguments stay in scalar registers
+  GemmArgs g = a.g[0];
+  void* C = a.C[0];
+  int first = a.start[0];
+#pragma unroll
+  for (int q = 1; q < kMaxMulti; ++q)
+    if (q < a.n && id >= a.start[q]) {
+      g = a.g[q];
+      C = a.C[q];
+      first = a.start[q];
+    }
+  gemm_dp_tile<TA, TB, OUT, WGM, WGN>(g, C, id - first, smem);
 }
 
 // Remainder form, for the tiles that do not fill a whole round of the machine.  The remaining tiles are cut into
@@ -953,24 +972,40 @@ static GemmArgs tn_args(const void* A, const void* B, int M, int N, int K) {
   return g;
 }
 
-// C0[M0,N0] += A0^T B0 and C1[M1,N1] += A1^T B1 (fp32 C, both operands [K, .]), sharing K: two weight
-// gradients whose inputs are ready at the same time.  In bf16 they run as one launch.
-int launch_gemm_tn_pair(int dtype, const void* A0, const void* B0, float* C0, int M0, int N0, const void* A1,
-                        const void* B1, float* C1, int M1, int N1, int K, hipStream_t st) {
-  if (dtype == PTDP_F32 || M0 == 0 || N0 == 0 || M1 == 0 || N1 == 0 ||
-      (size_t)M0 * K * 2 >= 0x7fffffffull || (size_t)N0 * K * 2 >= 0x7fffffffull ||
-      (size_t)M1 * K * 2 >= 0x7fffffffull || (size_t)N1 * K * 2 >= 0x7fffffffull) {
-    const int rc = launch_gemm(dtype, PTDP_GEMM_TN, A0, B0, C0, nullptr, M0, N0, K, 1, 1, nullptr, 0, st);
-    if (rc != PTDP_OK) return rc;
-    return launch_gemm(dtype, PTDP_GEMM_TN, A1, B1, C1, nullptr, M1, N1, K, 1, 1, nullptr, 0, st);
+// C_j[M_j,N_j] += A_j^T B_j for j < n <= 4 (fp32 C, both operands [K, .]), sharing K: weight gradients whose inputs
+// are all at hand.  In bf16 they run as one launch.
+int launch_gemm_tn_multi(int dtype, int n, const void* const* A, const void* const* B, float* const* C, const int* M,
+                         const int* N, int K, hipStream_t st) {
+  if (n <= 0 || n > kMaxMulti) return PTDP_E_INVALID_ARG;
+  bool one_by_one = dtype == PTDP_F32;
+  double flops = 0.0;
+  for (int j = 0; j < n; ++j) {
+    if (M[j] == 0 || N[j] == 0 || (size_t)M[j] * K * 2 >= 0x7fffffffull || (size_t)N[j] * K * 2 >= 0x7fffffffull) one_by_one = true;
+    flops += 2.0 * K * (double)M[j] * N[j];
   }
-  Launch L(PTDP_K_GEMM_TN, 2.0 * K * ((double)M0 * N0 + (double)M1 * N1), st);
-  const GemmArgs g0 = tn_args(A0, B0, M0, N0, K), g1 = tn_args(A1, B1, M1, N1, K);
-  auto kern = gemm_bf16_dp_pair_kernel<true, true, OUT_F32_RMW, kWGM, kWGN>;
+  if (one_by_one) {
+    for (int j = 0; j < n; ++j) {
+      const int rc = launch_gemm(dtype, PTDP_GEMM_TN, A[j], B[j], C[j], nullptr, M[j], N[j], K, 1, 1, nullptr, 0, st);
+      if (rc != PTDP_OK) return rc;
+    }
+    return PTDP_OK;
+  }
+  Launch L(PTDP_K_GEMM_TN, flops, st);
+  MultiArgs a;
+  a.n = n;
+  int at = 0;
+  for (int j = 0; j < kMaxMulti; ++j) {
+    const int q = j < n ? j : 0;   // unused slots repeat problem 0 (never selected)
+    a.g[j] = tn_args(A[q], B[q], M[q], N[q], K);
+    a.C[j] = C[q];
+    a.start[j] = at;
+    if (j < n) at += dp_blocks(a.g[j]);
+  }
+  a.start[kMaxMulti] = at;
+  auto kern = gemm_bf16_dp_multi_kernel<true, true, OUT_F32_RMW, kWGM, kWGN>;
   static once_flag_t done[kMaxDevices];
   if (set_dynamic_smem(reinterpret_cast<const void*>(kern), kGemmSmem, done) != PTDP_OK) return PTDP_E_HIP;
-  const int n0 = dp_blocks(g0);
-  hipLaunchKernelGGL(kern, dim3(n0 + dp_blocks(g1)), dim3(kGemmThreads), kGemmSmem, st, g0, (void*)C0, g1, (void*)C1, n0);
+  hipLaunchKernelGGL(kern, dim3(at), dim3(kGemmThreads), kGemmSmem, st, a);
   return L.status();
 }
 
