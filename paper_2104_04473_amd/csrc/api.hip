@@ -141,6 +141,19 @@ struct WsLayout {
   size_t off[WS_N];
   size_t total;
 };
+// scratch regions of WS_COLSUM, in the order the backward uses them: b_2, b_1, LayerNorm-2, b_o, b_qkv, LayerNorm-1
+constexpr int kColsumRegions = 6;
+static size_t colsum_region_bytes(const Dims& d, int i) {
+  size_t b = 0;
+  switch (i) {
+    case 0: case 3: b = colsum_scratch_bytes((int)d.T, (int)d.h); break;
+    case 1: b = colsum_scratch_bytes((int)d.T, (int)d.fp); break;
+    case 4: b = colsum_scratch_bytes((int)d.T, (int)(3 * d.hp)); break;
+    default: b = layernorm_bwd_scratch_bytes((int)d.T, (int)d.h); break;
+  }
+  return align256(b);
+}
+
 static WsLayout ws_layout(const ptdp_layer_cfg* c) {
   const Dims d = dims_of(c);
   size_t sz[WS_N];
@@ -149,12 +162,9 @@ static WsLayout ws_layout(const ptdp_layer_cfg* c) {
   sz[WS_CTX] = d.T * d.hp * d.esz;
   sz[WS_QKV] = d.T * 3 * d.hp * d.esz;
   sz[WS_DELTA] = (size_t)c->b * d.al * c->s * sizeof(float);
-  size_t cs = layernorm_bwd_scratch_bytes((int)d.T, (int)d.h);
-  const size_t c1 = colsum_scratch_bytes((int)d.T, (int)d.h);
-  if (c1 > cs) cs = c1;
-  const size_t c2 = colsum_scratch_bytes((int)d.T, (int)d.fp), c3 = colsum_scratch_bytes((int)d.T, (int)(3 * d.hp));
-  if (c2 > cs) cs = c2;
-  if (c3 > cs) cs = c3;
+  // the six column-sum producers of a layer's backward keep their partial sums until one launch finishes them all
+  size_t cs = 0;
+  for (int i = 0; i < kColsumRegions; ++i) cs += colsum_region_bytes(d, i);
   sz[WS_COLSUM] = cs;
   // partial tiles of GEMMs whose last, incomplete round of tiles is split along k
   sz[WS_SPLITK] = c->dtype == PTDP_BF16 ? gemm_workspace_bytes() : 0;
@@ -362,27 +372,33 @@ int ptdp_layer_backward(ptdp_chunk* ch, int layer, int64_t microbatch, const voi
   const int T = (int)d.T, h = (int)d.h, hp = (int)d.hp, fp = (int)d.fp;
   const uint32_t gl = (uint32_t)(ch->first_layer + layer);
   const int dt = c.dtype;
-  void* cs = wf(WS_COLSUM);
+  char* cs0 = (char*)wf(WS_COLSUM);
+  void* csr[kColsumRegions];
+  for (int i = 0; i < kColsumRegions; ++i) {
+    csr[i] = cs0;
+    cs0 += colsum_region_bytes(d, i);
+  }
+  ColsumBatch sums;   // the six second stages run as one launch at the end
   void* sk = wf(WS_SPLITK);
   const size_t skb = ws_field_bytes(ch->wl, WS_SPLITK);
 
   // MLP block.  The four weight gradients of the layer wait until all their inputs are there and run as one
   // launch at the end (each one's tiles fill the last, partial round of the ones before it); until then G, U2,
   // CTX, U and the gradients d(mo) [WS_DMO], dz [WS_BIG], do [WS_H1], dqkv [WS_QKV] stay untouched.
-  PTDP_TRY(launch_bda_bwd(dt, dy, wf(WS_DMO), G.b_2, cs, T, h, c.p_hidden,
-                          dropout_key(c.seed, gl, 1, (uint64_t)microbatch), st));
+  PTDP_TRY(launch_bda_bwd(dt, dy, wf(WS_DMO), G.b_2, csr[0], T, h, c.p_hidden,
+                          dropout_key(c.seed, gl, 1, (uint64_t)microbatch), st, &sums));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_DMO), P.w_2, wf(WS_BIG), nullptr, T, fp, h, 0, 0, sk, skb, st));
-  PTDP_TRY(launch_bias_gelu_bwd(dt, c.gelu_mode, wf(WS_BIG), sf(PTDP_STASH_Z), P.b_1, wf(WS_BIG), G.b_1, cs, T, fp, st));
+  PTDP_TRY(launch_bias_gelu_bwd(dt, c.gelu_mode, wf(WS_BIG), sf(PTDP_STASH_Z), P.b_1, wf(WS_BIG), G.b_1, csr[1], T, fp, st, &sums));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_BIG), P.w_1, wf(WS_H2), nullptr, T, h, fp, 0, 0, sk, skb, st));
   PTDP_TRY(launch_layernorm_bwd(dt, wf(WS_H2), sf(PTDP_STASH_X1), P.ln2_g, (const float*)sf(PTDP_STASH_MU2),
-                                (const float*)sf(PTDP_STASH_RSTD2), dy, wf(WS_X1), G.ln2_g, G.ln2_b, cs, T, h, st));
+                                (const float*)sf(PTDP_STASH_RSTD2), dy, wf(WS_X1), G.ln2_g, G.ln2_b, csr[2], T, h, st, &sums));
   // attention block
-  PTDP_TRY(launch_bda_bwd(dt, wf(WS_X1), wf(WS_H1), G.b_o, cs, T, h, c.p_hidden,
-                          dropout_key(c.seed, gl, 0, (uint64_t)microbatch), st));
+  PTDP_TRY(launch_bda_bwd(dt, wf(WS_X1), wf(WS_H1), G.b_o, csr[3], T, h, c.p_hidden,
+                          dropout_key(c.seed, gl, 0, (uint64_t)microbatch), st, &sums));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_H1), P.w_o, wf(WS_CTX), nullptr, T, hp, h, 0, 0, sk, skb, st));
   PTDP_TRY(launch_attn_bwd(dt, sf(PTDP_STASH_QKV), sf(PTDP_STASH_CTX), (const float*)sf(PTDP_STASH_LSE), wf(WS_CTX),
                            wf(WS_QKV), (float*)wf(WS_DELTA), c.s, c.b, (int)d.al, (int)d.dh, ch->mask, c.causal, st));
-  PTDP_TRY(launch_colsum(dt, wf(WS_QKV), G.b_qkv, cs, T, 3 * hp, st));
+  PTDP_TRY(launch_colsum(dt, wf(WS_QKV), G.b_qkv, csr[4], T, 3 * hp, st, &sums));
   PTDP_TRY(launch_gemm(dt, PTDP_GEMM_NT, wf(WS_QKV), P.w_qkv, wf(WS_H2), nullptr, T, h, 3 * hp, 0, 0, sk, skb, st));
   {
     const void* A[4] = {sf(PTDP_STASH_G), sf(PTDP_STASH_U2), sf(PTDP_STASH_U), sf(PTDP_STASH_CTX)};
@@ -392,7 +408,8 @@ int ptdp_layer_backward(ptdp_chunk* ch, int layer, int64_t microbatch, const voi
     PTDP_TRY(launch_gemm_tn_multi(dt, 4, A, B, C, M, N, T, st));
   }
   PTDP_TRY(launch_layernorm_bwd(dt, wf(WS_H2), sf(PTDP_STASH_X), P.ln1_g, (const float*)sf(PTDP_STASH_MU1),
-                                (const float*)sf(PTDP_STASH_RSTD1), wf(WS_X1), dx, G.ln1_g, G.ln1_b, cs, T, h, st));
+                                (const float*)sf(PTDP_STASH_RSTD1), wf(WS_X1), dx, G.ln1_g, G.ln1_b, csr[5], T, h, st, &sums));
+  PTDP_TRY(launch_colsum_batch(sums, st));
   return PTDP_OK;
 }
 

@@ -130,20 +130,36 @@ inline int set_dynamic_smem(const void* kern, int bytes, once_flag_t (&done)[kMa
   return PTDP_OK;
 }
 
+// Second stages of column sums that a caller wants run together: a backward kernel given a ColsumBatch only records
+// where its partial sums lie and what they are to be added to; launch_colsum_batch then finishes all of them in one
+// launch (each recorded job needs scratch of its own until then).
+struct ColsumJob {
+  const float* part;
+  int nparts, stride, width;
+  float* out0;
+  float* out1;   // second output (the partials' upper half) or null
+};
+constexpr int kMaxColsumJobs = 8;
+struct ColsumBatch {
+  ColsumJob job[kMaxColsumJobs];
+  int n = 0;
+};
+int launch_colsum_batch(const ColsumBatch& batch, hipStream_t st);
+
 // kernels (defined in the .hip files; all arguments validated by the callers in api.hip)
 int launch_layernorm_fwd(int dtype, const void* x, const void* gain, const void* bias, void* u, float* mu,
                          float* rstd, void* x_copy, int rows, int width, float eps, hipStream_t st);
 int launch_layernorm_bwd(int dtype, const void* du, const void* x, const void* gain, const float* mu,
                          const float* rstd, const void* resid, void* dx, float* dgain, float* dbias,
-                         void* scratch, int rows, int width, hipStream_t st);
+                         void* scratch, int rows, int width, hipStream_t st, ColsumBatch* defer = nullptr);
 int launch_bias_gelu_fwd(int dtype, int mode, const void* z, const void* bias, void* g, int rows, int width,
                          hipStream_t st);
 int launch_bias_gelu_bwd(int dtype, int mode, const void* dg, const void* z, const void* bias, void* dz,
-                         float* dbias, void* scratch, int rows, int width, hipStream_t st);
+                         float* dbias, void* scratch, int rows, int width, hipStream_t st, ColsumBatch* defer = nullptr);
 int launch_bda_fwd(int dtype, const void* in, const void* bias, const void* resid, void* out, int rows,
                    int width, float p, uint64_t key, hipStream_t st);
 int launch_bda_bwd(int dtype, const void* dout, void* din, float* dbias, void* scratch, int rows, int width,
-                   float p, uint64_t key, hipStream_t st);
+                   float p, uint64_t key, hipStream_t st, ColsumBatch* defer = nullptr);
 // same, with the column-sum partials in a static device array of kStaticScratchBytes (allocates nothing)
 constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
 int launch_bda_bwd_static(int dtype, const void* dout, void* din, float* dbias, int rows, int width, float p,
@@ -153,7 +169,8 @@ int launch_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t key, hipStre
 size_t colsum_scratch_bytes(int rows, int width);
 size_t layernorm_bwd_scratch_bytes(int rows, int width);   // scratch of launch_layernorm_bwd
 // out[width] (fp32) += column sums of in[rows, width]
-int launch_colsum(int dtype, const void* in, float* out, void* scratch, int rows, int width, hipStream_t st);
+int launch_colsum(int dtype, const void* in, float* out, void* scratch, int rows, int width, hipStream_t st,
+                  ColsumBatch* defer = nullptr);
 // ws / ws_bytes: optional scratch of gemm_workspace_bytes() for tiles that are split along k (may be null / 0)
 size_t gemm_workspace_bytes();
 // how a bf16 call is cut (host only): column tiles computed in whole rounds, then up to two groups of remainder

@@ -197,11 +197,11 @@ layernorm_bwd_kernel(const T* du, const T* __restrict__ x, const T* __restrict__
 // out[c] += sum over parts of part[p][c]  (second stage of every column sum; fixed order).
 // A workgroup owns 64 columns; its four waves each add a quarter of the parts (four independent partial
 // sums per lane keep loads in flight), and wave 0 adds the four quarter sums in order.
-__global__ void __launch_bounds__(256)
-colsum_finish_kernel(const float* __restrict__ part, int nparts, int stride, float* out0, float* out1, int width) {
+__device__ __forceinline__ void colsum_finish_block(const float* __restrict__ part, int nparts, int stride, float* out0, float* out1,
+                                                    int width, int blk) {
   __shared__ float red[2][4][64];
   const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + lane;
+  const int c = blk * 64 + lane;
   const int per = (nparts + 3) / 4, p0 = q * per, p1 = min(nparts, p0 + per);
   float a[4] = {0.f, 0.f, 0.f, 0.f}, b[4] = {0.f, 0.f, 0.f, 0.f};
   if (c < width) {
@@ -225,6 +225,31 @@ colsum_finish_kernel(const float* __restrict__ part, int nparts, int stride, flo
     out0[c] += (red[0][0][lane] + red[0][1][lane]) + (red[0][2][lane] + red[0][3][lane]);
     if (out1) out1[c] += (red[1][0][lane] + red[1][1][lane]) + (red[1][2][lane] + red[1][3][lane]);
   }
+}
+
+__global__ void __launch_bounds__(256)
+colsum_finish_kernel(const float* __restrict__ part, int nparts, int stride, float* out0, float* out1, int width) {
+  colsum_finish_block(part, nparts, stride, out0, out1, width, (int)blockIdx.x);
+}
+
+// several finishes in one launch: job j owns workgroups first[j] .. first[j+1]-1; same arithmetic as above
+struct ColsumBatchArgs {
+  ColsumJob job[kMaxColsumJobs];
+  int first[kMaxColsumJobs + 1];
+  int n;
+};
+__global__ void __launch_bounds__(256)
+colsum_finish_batch_kernel(ColsumBatchArgs a) {
+  const int id = (int)blockIdx.x;
+  ColsumJob j = a.job[0];   // constant indices only: the arguments stay in scalar registers
+  int first = 0;
+#pragma unroll
+  for (int q = 1; q < kMaxColsumJobs; ++q)
+    if (q < a.n && id >= a.first[q]) {
+      j = a.job[q];
+      first = a.first[q];
+    }
+  colsum_finish_block(j.part, j.nparts, j.stride, j.out0, j.out1, j.width, id - first);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -452,10 +477,35 @@ int launch_layernorm_fwd(int dtype, const void* x, const void* gain, const void*
 }
 
 static int colsum_finish(const float* part, int nparts, int stride, float* out0, float* out1, int width,
-                         hipStream_t st) {
+                         hipStream_t st, ColsumBatch* defer = nullptr) {
+  if (defer) {
+    if (defer->n >= kMaxColsumJobs) return PTDP_E_INVALID_ARG;
+    defer->job[defer->n++] = ColsumJob{part, nparts, stride, width, out0, out1};
+    return PTDP_OK;
+  }
   Launch L(PTDP_K_COLSUM, (double)nparts * stride * sizeof(float), st);
   hipLaunchKernelGGL(colsum_finish_kernel, dim3((width + 63) / 64), dim3(256), 0, st, part, nparts, stride, out0,
                      out1, width);
+  return L.status();
+}
+
+int launch_colsum_batch(const ColsumBatch& batch, hipStream_t st) {
+  if (batch.n == 0) return PTDP_OK;
+  ColsumBatchArgs a;
+  a.n = batch.n;
+  double bytes = 0.0;
+  int at = 0;
+  for (int j = 0; j < kMaxColsumJobs; ++j) {
+    a.job[j] = batch.job[j < batch.n ? j : 0];   // unused slots repeat job 0 (never selected)
+    a.first[j] = at;
+    if (j < batch.n) {
+      at += (batch.job[j].width + 63) / 64;
+      bytes += (double)batch.job[j].nparts * batch.job[j].stride * sizeof(float);
+    }
+  }
+  a.first[kMaxColsumJobs] = at;
+  Launch L(PTDP_K_COLSUM, bytes, st);
+  hipLaunchKernelGGL(colsum_finish_batch_kernel, dim3(at), dim3(256), 0, st, a);
   return L.status();
 }
 
@@ -471,7 +521,7 @@ size_t layernorm_bwd_scratch_bytes(int rows, int width) {
 template <typename T>
 static int ln_bwd_t(const void* du, const void* x, const void* gain, const float* mu, const float* rstd,
                     const void* resid, void* dx, float* dgain, float* dbias, void* scratch, int rows, int width,
-                    hipStream_t st) {
+                    hipStream_t st, ColsumBatch* defer) {
   constexpr int N = Vec16<T>::N;
   int vpt;
   const int threads = ln_threads(width / N, &vpt);
@@ -498,16 +548,16 @@ static int ln_bwd_t(const void* du, const void* x, const void* gain, const float
 #undef PTDP_LN_BWD
     if (L.status() != PTDP_OK) return L.status();
   }
-  return colsum_finish(part, nblk, 2 * width, dgain, dbias, width, st);
+  return colsum_finish(part, nblk, 2 * width, dgain, dbias, width, st, defer);
 }
 
 int launch_layernorm_bwd(int dtype, const void* du, const void* x, const void* gain, const float* mu,
                          const float* rstd, const void* resid, void* dx, float* dgain, float* dbias,
-                         void* scratch, int rows, int width, hipStream_t st) {
+                         void* scratch, int rows, int width, hipStream_t st, ColsumBatch* defer) {
   if (rows == 0) return PTDP_OK;
   return dtype == PTDP_BF16
-             ? ln_bwd_t<bf16_t>(du, x, gain, mu, rstd, resid, dx, dgain, dbias, scratch, rows, width, st)
-             : ln_bwd_t<float>(du, x, gain, mu, rstd, resid, dx, dgain, dbias, scratch, rows, width, st);
+             ? ln_bwd_t<bf16_t>(du, x, gain, mu, rstd, resid, dx, dgain, dbias, scratch, rows, width, st, defer)
+             : ln_bwd_t<float>(du, x, gain, mu, rstd, resid, dx, dgain, dbias, scratch, rows, width, st, defer);
 }
 
 static inline int stream_grid(size_t total_vec) {
@@ -539,7 +589,7 @@ int launch_bias_gelu_fwd(int dtype, int mode, const void* z, const void* bias, v
 
 template <typename T>
 static int gelu_bwd_t(int mode, const void* dg, const void* z, const void* bias, void* dz, float* dbias,
-                      void* scratch, int rows, int width, hipStream_t st) {
+                      void* scratch, int rows, int width, hipStream_t st, ColsumBatch* defer) {
   constexpr int N = Vec16<T>::N;
   const int nvec = width / N;
   const dim3 grid((nvec + 255) / 256, (rows + kColRows - 1) / kColRows);
@@ -554,14 +604,14 @@ static int gelu_bwd_t(int mode, const void* dg, const void* z, const void* bias,
                          (const T*)z, (const T*)bias, (T*)dz, part, rows, width);
     if (L.status() != PTDP_OK) return L.status();
   }
-  return colsum_finish(part, grid.y, width, dbias, nullptr, width, st);
+  return colsum_finish(part, grid.y, width, dbias, nullptr, width, st, defer);
 }
 
 int launch_bias_gelu_bwd(int dtype, int mode, const void* dg, const void* z, const void* bias, void* dz,
-                         float* dbias, void* scratch, int rows, int width, hipStream_t st) {
+                         float* dbias, void* scratch, int rows, int width, hipStream_t st, ColsumBatch* defer) {
   if (rows == 0) return PTDP_OK;
-  return dtype == PTDP_BF16 ? gelu_bwd_t<bf16_t>(mode, dg, z, bias, dz, dbias, scratch, rows, width, st)
-                            : gelu_bwd_t<float>(mode, dg, z, bias, dz, dbias, scratch, rows, width, st);
+  return dtype == PTDP_BF16 ? gelu_bwd_t<bf16_t>(mode, dg, z, bias, dz, dbias, scratch, rows, width, st, defer)
+                            : gelu_bwd_t<float>(mode, dg, z, bias, dz, dbias, scratch, rows, width, st, defer);
 }
 
 template <typename T>
@@ -585,7 +635,7 @@ int launch_bda_fwd(int dtype, const void* in, const void* bias, const void* resi
 
 template <typename T>
 static int bda_bwd_t(const void* dout, void* din, float* dbias, void* scratch, int rows, int width, float p,
-                     uint64_t key, hipStream_t st) {
+                     uint64_t key, hipStream_t st, ColsumBatch* defer) {
   constexpr int N = Vec16<T>::N;
   const int nvec = width / N;
   const dim3 grid((nvec + 255) / 256, (rows + kColRows - 1) / kColRows);
@@ -596,14 +646,14 @@ static int bda_bwd_t(const void* dout, void* din, float* dbias, void* scratch, i
                        p > 0.f ? dropout_threshold(p) : 0u, 1.0f / (1.0f - p));
     if (L.status() != PTDP_OK) return L.status();
   }
-  return colsum_finish(part, grid.y, width, dbias, nullptr, width, st);
+  return colsum_finish(part, grid.y, width, dbias, nullptr, width, st, defer);
 }
 
 int launch_bda_bwd(int dtype, const void* dout, void* din, float* dbias, void* scratch, int rows, int width, float p,
-                   uint64_t key, hipStream_t st) {
+                   uint64_t key, hipStream_t st, ColsumBatch* defer) {
   if (rows == 0) return PTDP_OK;
-  return dtype == PTDP_BF16 ? bda_bwd_t<bf16_t>(dout, din, dbias, scratch, rows, width, p, key, st)
-                            : bda_bwd_t<float>(dout, din, dbias, scratch, rows, width, p, key, st);
+  return dtype == PTDP_BF16 ? bda_bwd_t<bf16_t>(dout, din, dbias, scratch, rows, width, p, key, st, defer)
+                            : bda_bwd_t<float>(dout, din, dbias, scratch, rows, width, p, key, st, defer);
 }
 
 // Column-sum partials for callers that may not allocate: one array per device, kept until the process
@@ -633,11 +683,11 @@ int launch_bda_bwd_static(int dtype, const void* dout, void* din, float* dbias, 
   void* ptr = nullptr;
   const int rc = static_scratch(&ptr);
   if (rc != PTDP_OK) return rc;
-  return launch_bda_bwd(dtype, dout, din, dbias, ptr, rows, width, p, key, st);
+  return launch_bda_bwd(dtype, dout, din, dbias, ptr, rows, width, p, key, st, nullptr);
 }
 
 template <typename T>
-static int colsum_t(const void* in, float* out, void* scratch, int rows, int width, hipStream_t st) {
+static int colsum_t(const void* in, float* out, void* scratch, int rows, int width, hipStream_t st, ColsumBatch* defer) {
   constexpr int N = Vec16<T>::N;
   const dim3 grid((width / N + 255) / 256, (rows + kColRows - 1) / kColRows);
   float* part = (float*)scratch;
@@ -646,13 +696,14 @@ static int colsum_t(const void* in, float* out, void* scratch, int rows, int wid
     hipLaunchKernelGGL((colsum_rows_kernel<T>), grid, dim3(256), 0, st, (const T*)in, part, rows, width);
     if (L.status() != PTDP_OK) return L.status();
   }
-  return colsum_finish(part, grid.y, width, out, nullptr, width, st);
+  return colsum_finish(part, grid.y, width, out, nullptr, width, st, defer);
 }
 
-int launch_colsum(int dtype, const void* in, float* out, void* scratch, int rows, int width, hipStream_t st) {
+int launch_colsum(int dtype, const void* in, float* out, void* scratch, int rows, int width, hipStream_t st,
+                  ColsumBatch* defer) {
   if (rows == 0) return PTDP_OK;
-  return dtype == PTDP_BF16 ? colsum_t<bf16_t>(in, out, scratch, rows, width, st)
-                            : colsum_t<float>(in, out, scratch, rows, width, st);
+  return dtype == PTDP_BF16 ? colsum_t<bf16_t>(in, out, scratch, rows, width, st, defer)
+                            : colsum_t<float>(in, out, scratch, rows, width, st, defer);
 }
 
 int launch_dropout_mask(uint8_t* keep, int64_t n, float p, uint64_t key, hipStream_t st) {
