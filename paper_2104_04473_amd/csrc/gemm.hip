@@ -85,41 +85,76 @@ typedef __attribute__((address_space(3))) void lds_void_t;
 
 constexpr uint32_t kOob = 0x80000000u;  // beyond any num_records this kernel accepts (< 2 GiB)
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+// Buffer descriptor (raw, no stride, no swizzle): 48-bit base, bytes, data format dword.
+typedef uint32_t rsrc_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(p);
+  rsrc_t r = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
+  return r;
+}
+__device__ __forceinline__ uint32_t lds_offset(const char* p) {
+  return (uint32_t)reinterpret_cast<uintptr_t>((lds_void_t*)p);
 }
 
-// one wave-wide 1 KiB load into LDS at `dst` (wave-uniform); lane i lands at dst + 16*i
-__device__ __forceinline__ void load_lds_16(__amdgpu_buffer_rsrc_t r, char* dst, uint32_t voff) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_t*)dst, 16, voff, 0, 0, 0);
+// Global -> LDS loads (16 bytes per lane, lane i lands at dst + 16*i; dst wave-uniform) are written as assembly:
+// the compiler makes every LDS read that it cannot prove disjoint (all transposing reads) wait for every such
+// load in flight, which would cut the distance between request and use from a k-tile to a fraction of one.  The
+// main loops order these loads themselves: an explicit vmcnt(0) wait and a barrier stand between a request and
+// the first read of what it brings, and no other vector-memory access is in flight while one of them is.
+__device__ __forceinline__ void load_lds_16(rsrc_t r, char* dst, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_offset(dst)), "v"(voff), "s"(r) : "memory", "m0");
+}
+__device__ __forceinline__ void load_lds_4(rsrc_t r, char* dst, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+               :: "s"(lds_offset(dst)), "v"(voff), "s"(r) : "memory", "m0");
+}
+// four wave-loads whose destinations lie 1 KiB apart: the instruction's offset field moves the destination (and
+// the source: the lane offsets passed in are 0, 1024, 2048, 3072 bytes short); soff is added to the source only
+__device__ __forceinline__ void load_lds_16x4(rsrc_t r, char* dst, uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3,
+                                              uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+               "buffer_load_dwordx4 %1, %5, %6 offen lds\n\t"
+               "buffer_load_dwordx4 %2, %5, %6 offen offset:1024 lds\n\t"
+               "buffer_load_dwordx4 %3, %5, %6 offen offset:2048 lds\n\t"
+               "buffer_load_dwordx4 %4, %5, %6 offen offset:3072 lds"
+               :: "s"(lds_offset(dst)), "v"(v0), "v"(v1), "v"(v2), "v"(v3), "s"(r), "s"(soff) : "memory", "m0");
 }
 
 // One 256-row operand tile of 64 k (32 KiB) is filled by 32 wave-loads of 1 KiB; wave w of NW issues
 // wave-loads w*LPW .. w*LPW+LPW-1.
+// A k-tile that lies inside K whole is requested with as few instructions as the hardware allows, because every
+// one of them takes an issue slot from the MFMAs: the lane offsets are loop constants, the k advance rides in the
+// scalar offset, and the destinations of four consecutive wave-loads differ only in the instruction's offset
+// field (which moves the source too, so it is taken out of the lane offset beforehand); the last, partial k-tile
+// and operands with rows shorter than 256 elements take the general form with its per-lane checks.
 constexpr int BK = 64;
 template <bool KSLOW, int NW> struct TileLoad {
   static constexpr int LPW = 32 / NW;
-  uint32_t off[LPW];   // byte offset of the lane's chunk at k-tile 0, or kOob if its row is out of range
+  uint32_t offm[LPW];  // byte offset of the lane's chunk at k-tile 0 minus 1024 * (i % 4), or kOob if its row is out of range
   uint32_t kstep;      // byte advance per k-tile
   int kfirst;          // k of wave-load 0's chunk (k-contiguous: first k of the chunk; k-slow: the k-row)
+  bool plain;          // no offset above goes negative
 
   // the descriptor's base is the block's first row (k-contiguous: base + row0*ld; k-slow: base + row0)
   __device__ __forceinline__ void init(size_t ld, int rows_left, int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
       const int li = wave * LPW + i;
+      const uint32_t imm = (uint32_t)(i & 3) * 1024u;
       if (!KSLOW) {
         const int row = li * 8 + (lane >> 3);
         const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-        off[i] = row < rows_left ? (uint32_t)(((size_t)row * ld + chunk * 8) * 2) : kOob;
+        offm[i] = row < rows_left ? (uint32_t)(((size_t)row * ld + chunk * 8) * 2) - imm : kOob;
       } else {
         const int k = li * 2 + (lane >> 5);
         const int chunk = (lane & 31) ^ (4 * (k & 3)) ^ (2 * ((k >> 3) & 1));
-        off[i] = chunk * 8 < rows_left ? (uint32_t)(((size_t)k * ld + chunk * 8) * 2) : kOob;
+        offm[i] = chunk * 8 < rows_left ? (uint32_t)(((size_t)k * ld + chunk * 8) * 2) - imm : kOob;
       }
     }
     kstep = KSLOW ? (uint32_t)(BK * ld * 2) : (uint32_t)(BK * 2);
     kfirst = KSLOW ? wave * LPW * 2 + (lane >> 5) : 0;
+    plain = ld >= 256;   // row (or k-row) i of a wave-load starts at least 1024 * (i % 4) bytes into the block
   }
   // k of the lane's data in wave-load i: k-contiguous -> depends on the row's swizzle, recomputed here
   __device__ __forceinline__ int kpos(int i, int wave, int lane) const {
@@ -128,11 +163,18 @@ template <bool KSLOW, int NW> struct TileLoad {
     return ((lane & 7) ^ ((row >> 1) & 7)) * 8;
   }
   // k-tiles past the end of K come back as zeros (every lane out of range)
-  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t r, char* tile, int wave, int lane, int kt, int K) {
+  __device__ __forceinline__ void issue(rsrc_t r, char* tile, int wave, int lane, int kt, int K) {
+    if (plain && (kt + 1) * BK <= K) {
+      const uint32_t koff = (uint32_t)kt * kstep;
 #pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-      const bool ok = off[i] != kOob && kt * BK + kpos(i, wave, lane) < K;
-      load_lds_16(r, tile + (wave * LPW + i) * 1024, ok ? off[i] + (uint32_t)kt * kstep : kOob);
+      for (int i = 0; i < LPW; i += 4)
+        load_lds_16x4(r, tile + (wave * LPW + i) * 1024, offm[i], offm[i + 1], offm[i + 2], offm[i + 3], koff);
+    } else {
+#pragma unroll
+      for (int i = 0; i < LPW; ++i) {
+        const bool ok = offm[i] != kOob && kt * BK + kpos(i, wave, lane) < K;
+        load_lds_16(r, tile + (wave * LPW + i) * 1024, ok ? offm[i] + (uint32_t)(i & 3) * 1024u + (uint32_t)kt * kstep : kOob);
+      }
     }
   }
 };
@@ -247,12 +289,11 @@ template <bool TA, bool TB> struct PanelTouch {
     }
   }
   // kt: the k-tile whose demand request is being issued
-  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, char* smem, int wave, int kt, int kend) const {
+  __device__ __forceinline__ void issue(rsrc_t ra, rsrc_t rb, char* smem, int wave, int kt, int kend) const {
     if (!on) return;
     const int kt2 = kt + kTouchAhead;
     const bool ok = off != kOob && kt2 * BK < kend;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? ra : rb, (lds_void_t*)(smem + 2 * kStageBytes + wave * 256), 4,
-                                             ok ? off + (uint32_t)kt2 * step : kOob, 0, 0, 0);
+    load_lds_4(is_a ? ra : rb, smem + 2 * kStageBytes + wave * 256, ok ? off + (uint32_t)kt2 * step : kOob);
   }
 };
 
@@ -279,8 +320,8 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kB
   const bf16_t* b_base = TB ? g.B + n0 : g.B + (size_t)n0 * g.ldb;
   const size_t a_left = (size_t)(g.a_end - reinterpret_cast<const char*>(a_base));
   const size_t b_left = (size_t)(g.b_end - reinterpret_cast<const char*>(b_base));
-  const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, (uint32_t)(a_left < 0x7fffffffu ? a_left : 0x7fffffffu));
-  const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, (uint32_t)(b_left < 0x7fffffffu ? b_left : 0x7fffffffu));
+  const rsrc_t ra = make_rsrc(a_base, (uint32_t)(a_left < 0x7fffffffu ? a_left : 0x7fffffffu));
+  const rsrc_t rb = make_rsrc(b_base, (uint32_t)(b_left < 0x7fffffffu ? b_left : 0x7fffffffu));
   const int kend = min(g.K, kt1 * BK);  // k-tiles from kt1 on read as zeros
 
   TileLoad<TA, NW> la;
@@ -451,8 +492,8 @@ __device__ __forceinline__ void gemm_mainloop16(f32x4_t (&acc)[kBM / WGM / 16][k
   const bf16_t* b_base = TB ? g.B + n0 : g.B + (size_t)n0 * g.ldb;
   const size_t a_left = (size_t)(g.a_end - reinterpret_cast<const char*>(a_base));
   const size_t b_left = (size_t)(g.b_end - reinterpret_cast<const char*>(b_base));
-  const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_base, (uint32_t)(a_left < 0x7fffffffu ? a_left : 0x7fffffffu));
-  const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_base, (uint32_t)(b_left < 0x7fffffffu ? b_left : 0x7fffffffu));
+  const rsrc_t ra = make_rsrc(a_base, (uint32_t)(a_left < 0x7fffffffu ? a_left : 0x7fffffffu));
+  const rsrc_t rb = make_rsrc(b_base, (uint32_t)(b_left < 0x7fffffffu ? b_left : 0x7fffffffu));
   const int kend = min(g.K, kt1 * BK);  // k-tiles from kt1 on read as zeros
 
   TileLoad<TA, NW> la;
