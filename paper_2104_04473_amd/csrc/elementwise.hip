@@ -102,13 +102,15 @@ layernorm_bwd_kernel(const T* du, const T* __restrict__ x, const T* __restrict__
   for (int r = r0; r < r1; ++r) {
     const size_t base = (size_t)r * width;
     const float m = mu[r], rs = rstd[r];
-    Vec16<T> a[VPT], b[VPT];
+    // the residual gradient is only wanted after the reduction, but requested here: one round trip per row
+    Vec16<T> a[VPT], b[VPT], rr[VPT];
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
       const int c = threadIdx.x + i * blockDim.x;
       if (c < nvec) {
         a[i].load(du + base + (size_t)c * N);
         b[i].load(x + base + (size_t)c * N);
+        if (resid) rr[i].load(resid + base + (size_t)c * N);
       }
     }
     __syncthreads();   // gain row visible (first row); `red` of the previous row no longer read
@@ -166,9 +168,7 @@ layernorm_bwd_kernel(const T* du, const T* __restrict__ x, const T* __restrict__
         b[i].unpack(xf);
         g.unpack(gf);
         if (resid) {
-          Vec16<T> rr;
-          rr.load(resid + base + (size_t)c * N);
-          rr.unpack(of);
+          rr[i].unpack(of);
         } else {
 #pragma unroll
           for (int j = 0; j < N; ++j) of[j] = 0.f;
