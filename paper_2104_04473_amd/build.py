@@ -23,6 +23,11 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hi
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+# per-source additions.  attention.hip: one wave per SIMD, so every instruction counts; with MFMA results in the
+# vector registers (instead of the accumulation registers) the softmax arithmetic reads them in place and the main
+# loops lose a quarter of their instructions (v_accvgpr moves).
+EXTRA_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
 LIB_ASAN = os.path.join(HERE, "libptdp_asan.so")
 SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
              "-fno-omit-frame-pointer", "-g"]
@@ -31,7 +36,7 @@ SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=und
 def _compile(src, sanitize=False):
     obj = os.path.join(HERE, "_build", ("asan_" if sanitize else "") + src.replace(".hip", ".o"))
     flags = [f if f != "-O3" else "-O1" for f in FLAGS] + SAN_FLAGS if sanitize else FLAGS
-    cmd = [HIPCC] + flags + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + flags + EXTRA_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed on %s:\n%s\n%s" % (src, r.stdout, r.stderr))
