@@ -5,9 +5,10 @@
 //   mode NT: C[M,N] = A[M,K] B[N,K]^T        input grad   dX = dY W^T
 //   mode TN: C[M,N] = A[K,M]^T B[K,N]        weight grad  dW = X^T dY
 //
-// bf16 path: v_mfma_f32_32x32x16_bf16 (gfx950), 256 x 256 block tile, multi-stage LDS ring filled by
-// direct global->LDS loads.  An operand whose reduction index is the slow memory index (B in NN, both
-// in TN) stays in its memory order in LDS and is gathered into MFMA fragments by transposing LDS reads.
+// bf16 path (gfx950): v_mfma_f32_16x16x32_bf16 for NN and NT, v_mfma_f32_32x32x16_bf16 for TN; 256 x 256 block
+// tile, two LDS stages of 64 k filled by direct global->LDS loads.  An operand whose reduction index is the slow
+// memory index (B in NN, both in TN) stays in its memory order in LDS and is gathered into MFMA fragments by
+// transposing LDS reads.
 // fp32 path: a plain LDS-tiled FMA kernel (correctness configuration only).
 #include "common.h"
 
@@ -68,17 +69,18 @@ gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ B, float*
 
 // ------------------------------------------------------------------------------------------------
 // bf16 MFMA kernel: global -> LDS without passing through registers (buffer_load ... lds, 16 bytes
-// per lane), 256 x 256 x BKT block tile, 8 waves (2 x 4, 128 x 64 each), a ring of NST LDS stages.
+// per lane), 256 x 256 x 64 block tile, 8 waves (2 x 4, 128 x 64 each), two LDS stages.
 // Out-of-range lanes use an offset beyond the buffer's num_records, for which the hardware returns
 // zeros.
 //
 // LDS tile layouts:
-//   k-contiguous operand: [row][BKT/8 chunks of 16 B]; chunk c of row r sits in slot c ^ f(r), f chosen
+//   k-contiguous operand: [row][8 chunks of 16 B]; chunk c of row r sits in slot c ^ f(r), f chosen
 //     so that 16 neighbouring rows of one fragment read fall into 16 different 16-byte bank groups.
 //   k-slow operand (memory [k][row]): [k][32 chunks of 16 B] (512 B per k); chunk c of k-row k sits in
 //     slot c ^ (4 * (k & 3)) ^ (2 * ((k >> 3) & 1)): the four k-rows that one group of 16 lanes gathers land in
-//     different bank groups, and so do k-rows 8 apart, which the 16x16x32 fragments read in the same cycle.  MFMA fragments are gathered with ds_read_b64_tr_b16: within 16 lanes,
-//     lane i receives element (i & 3) of the 8-byte rows addressed by lanes (i >> 2) + {0, 4, 8, 12}.
+//     different bank groups, and so do k-rows 8 apart, which the 16x16x32 fragments read in the same cycle.
+//     MFMA fragments are gathered with ds_read_b64_tr_b16: within 16 lanes, lane i receives element (i & 3) of
+//     the 8-byte rows addressed by lanes (i >> 2) + {0, 4, 8, 12}.
 // ------------------------------------------------------------------------------------------------
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
 typedef __attribute__((address_space(3))) void lds_void_t;
@@ -306,9 +308,10 @@ template <bool TA, bool TB> struct PanelTouch {
 // on the critical path (k-slow operands) the loads go out after the next tile's first fragment reads,
 // otherwise before them (measured: +9..14 % over issuing them at the top of the next iteration).
 // Measured on copies of this loop with parts removed (NT, all 256 CUs busy, per k-tile): MFMAs alone 1.28 us
-// (the chip's power limit on changing operands; 0.96 us on a lone CU), fragment reads +0.08, the loads +0.27,
-// the barrier +0.12; the loads have always landed when the barrier is reached (dropping the wait changes
-// nothing), so neither more stages nor an earlier request shorten a k-tile.
+// (the chip's power limit on changing operands; 0.96 us on a lone CU), fragment reads +0.08, the barrier +0.12,
+// the loads +0.27 in the compiler's form (most of it the issue slots of their address arithmetic: see TileLoad);
+// the loads have always landed when the barrier is reached (dropping the wait changes nothing), so neither more
+// stages nor an earlier request shorten a k-tile.
 template <bool TA, bool TB, int WGM, int WGN>
 __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kBN / WGN / 32], const GemmArgs& g,
                                               int m0, int n0, int kt0, int kt1, char* smem, int share) {
