@@ -218,7 +218,7 @@ template <int DH> struct TileRegs {
   __device__ __forceinline__ void load(const bf16_t* __restrict__ src, size_t rs, int row0, int s) {
 #pragma unroll
     for (int i = 0; i < TileGeom<DH>::NCH; ++i) {
-      const int c = threadIdx.x + i * kAttnThreads;
+      const int c = (threadIdx.x & (kAttnThreads - 1)) + i * kAttnThreads;
       const int row = c / (DH / 8), ch = c % (DH / 8);
       // branch-free: read a clamped (always valid) row, then blank it if it is past the end, so that
       // the loads of a tile are issued back to back
@@ -231,7 +231,7 @@ template <int DH> struct TileRegs {
   __device__ __forceinline__ void store(char* lds) const {
 #pragma unroll
     for (int i = 0; i < TileGeom<DH>::NCH; ++i) {
-      const int c = threadIdx.x + i * kAttnThreads;
+      const int c = (threadIdx.x & (kAttnThreads - 1)) + i * kAttnThreads;
       const int row = c / (DH / 8), ch = c % (DH / 8);
       *reinterpret_cast<uint4*>(lds + row * TileGeom<DH>::STRIDE + ch * 16) = v[i];
     }
@@ -247,7 +247,7 @@ template <int DH> struct TileMap {
   __device__ __forceinline__ void init(size_t rs) {
 #pragma unroll
     for (int i = 0; i < TileGeom<DH>::NCH; ++i) {
-      const int c = threadIdx.x + i * kAttnThreads;
+      const int c = (threadIdx.x & (kAttnThreads - 1)) + i * kAttnThreads;
       const int row = c / (DH / 8), ch = c % (DH / 8);
       src[i] = (uint32_t)(row * rs + ch * 8);
       dst[i] = (uint32_t)(row * TileGeom<DH>::STRIDE + ch * 16);
@@ -503,13 +503,17 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
 // needs atomics: one owns 64 queries and produces dQ, one owns 64 keys and produces dK and dV.
 //   dP = dO V^T, dS = P o (dP - delta), dQ = dS K / sqrt(dh), dK = dS^T Q / sqrt(dh), dV = P^T dO
 // ------------------------------------------------------------------------------------------------
-template <int DH, bool CAUSAL>
-__global__ void __launch_bounds__(kAttnThreads, DH >= 96 ? 1 : 2)
+// dQ: a workgroup owns 64 queries.  NP = 2: it is two pairs of waves; pair p walks every second 64-key tile with
+// tiles of its own in LDS and pair 1 hands its sums to pair 0 at the end (see the dK/dV kernel below for when).
+template <int DH, bool CAUSAL, int NP>
+__global__ void __launch_bounds__(NP * kAttnThreads, DH >= 96 ? 1 : 2)
 attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
                  const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads,
                  const uint8_t* __restrict__ mask) {
   constexpr int NKK = DH / 16, NDT = DH / 32;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(16))) char smem_all[];
+  const int pair = NP == 2 ? threadIdx.x >> 7 : 0;
+  char* smem = smem_all + pair * 2 * TileGeom<DH>::BYTES;
   char* k_lds = smem;                          // K [key][dh]: S^T = K Q^T directly, dQ^T = K^T dS^T through tr reads
   char* v_lds = smem + TileGeom<DH>::BYTES;    // V [key][dh]: dP^T = V dO^T
 
@@ -517,7 +521,7 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
   int qblk, e, j;
   if (!attn_map(blockIdx.x, nqb, heads, b, &qblk, &e, &j)) return;
   qblk = nqb - 1 - qblk;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
+  const int wave = (threadIdx.x >> 6) & 1, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
   const int hp = heads * DH;
   const size_t rs = (size_t)b * 3 * hp;
   const bf16_t* base = qkv + (size_t)j * 3 * hp + (size_t)e * DH;
@@ -549,17 +553,25 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
   TileMap<DH> map;
   map.init(rs);
   TileRegs<DH> kr, vr;
-  map.load(kr, base + hp, rs, 0, s);
-  map.load(vr, base + 2 * hp, rs, 0, s);
-  for (int kt = 0; kt < ntiles; ++kt) {
+  if (pair < ntiles) {
+    map.load(kr, base + hp, rs, pair * kBKV, s);
+    map.load(vr, base + 2 * hp, rs, pair * kBKV, s);
+  }
+  // both pairs take the same number of steps (the barriers are the workgroup's); a pair without a tile idles
+  for (int kt0 = 0; kt0 < ntiles; kt0 += NP) {
+    const int kt = kt0 + pair;
+    const bool have = kt < ntiles;
     const int key0 = kt * kBKV;
     __syncthreads();
-    map.store(kr, k_lds);
-    map.store(vr, v_lds);
+    if (have) {
+      map.store(kr, k_lds);
+      map.store(vr, v_lds);
+    }
     __syncthreads();
-    if (kt + 1 < ntiles) {
-      map.load(kr, base + hp, rs, key0 + kBKV, s);
-      map.load(vr, base + 2 * hp, rs, key0 + kBKV, s);
+    if (!have) continue;
+    if (kt + NP < ntiles) {
+      map.load(kr, base + hp, rs, key0 + NP * kBKV, s);
+      map.load(vr, base + 2 * hp, rs, key0 + NP * kBKV, s);
     }
     if (CAUSAL && key0 > q_first + 31) continue;
     const bool diag = key0 + kBKV - 1 > q_first;   // only tiles on the diagonal need the causal mask
@@ -609,18 +621,50 @@ attn_bwd_dq_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx
         for (int ks = 0; ks < 2; ++ks)
           acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(k_lds, d, sub, ks, lane), dsf[sub][ks], acc[d], 0, 0, 0);
   }
+  if constexpr (NP == 2) {
+    // pair 1's sums join pair 0's: register r of lane l of wave w at sum[w][r][l]
+    __syncthreads();   // every wave is done with the tiles
+    float* sum = reinterpret_cast<float*>(smem_all) + wave * (NDT * 16 * 64) + lane;
+    if (pair == 1) {
+#pragma unroll
+      for (int d = 0; d < NDT; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[(d * 16 + r) * 64] = acc[d][r];
+    }
+    __syncthreads();
+    if (pair == 1) return;
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[d][r] += sum[(d * 16 + r) * 64];
+  }
   if (valid) store_cols<NDT>(dqkv + (size_t)my_q * rs + (size_t)j * 3 * hp + (size_t)e * DH, acc, scale, half);
 }
 
 constexpr int kMaskLdsStride = 68;   // bytes per key row of the staged mask tile ([key][query], padded)
 
-template <int DH, bool CAUSAL>
-__global__ void __launch_bounds__(kAttnThreads)
+// dK/dV: a workgroup owns 64 keys; wave w of a pair owns keys 32 w .. 32 w + 31.  NP = 1: one pair of waves walks all
+// 64-query tiles.  NP = 2: two pairs; pair p walks every second tile (first + p, first + p + 2, ...) with tiles of its
+// own in LDS, and at the end pair 1 hands its sums to pair 0 through LDS, added in that fixed order.  The workgroup
+// that owns the first keys of a causal head walks all query tiles and the launch lasts at least as long as it does:
+// two pairs halve that path, at the price of one barrier domain per CU instead of two independent ones.  The launch
+// code takes NP = 2 when all workgroups of the one-pair form would be resident at once (the longest one then sets
+// the time: GPT-3-shaped shard, 12 heads: backward 0.213 -> 0.152 ms) and NP = 1 otherwise (1T-shaped shard, 20
+// heads of 160: 0.331 against 0.343 ms).
+template <int DH, bool CAUSAL> struct DkvLds {
+  static constexpr int kPair = 2 * TileGeom<DH>::BYTES + 2 * kBKV * (int)sizeof(float) + (CAUSAL ? 0 : kBQ * kMaskLdsStride);
+  static constexpr int kSum = 2 * (DH / 32) * 16 * 64 * (int)sizeof(float);   // one wave's dK and dV
+  static constexpr int kBytes2 = 2 * kPair > 2 * kSum ? 2 * kPair : 2 * kSum;
+};
+template <int DH, bool CAUSAL, int NP>
+__global__ void __launch_bounds__(NP * kAttnThreads)
 attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dctx, const float* __restrict__ lse,
                   const float* __restrict__ delta, bf16_t* __restrict__ dqkv, int s, int b, int heads,
                   const uint8_t* __restrict__ mask) {
   constexpr int NKK = DH / 16, NDT = DH / 32;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(16))) char smem_all[];
+  const int pair = NP == 2 ? threadIdx.x >> 7 : 0, tid = threadIdx.x & (kAttnThreads - 1);
+  char* smem = smem_all + pair * DkvLds<DH, CAUSAL>::kPair;
   char* q_lds = smem;                           // Q  [query][dh]: S = Q K^T directly, dK^T = Q^T dS through tr reads
   char* do_lds = smem + TileGeom<DH>::BYTES;    // dO [query][dh]: dP = dO V^T directly, dV^T = dO^T P through tr reads
   float* lse_lds = reinterpret_cast<float*>(smem + 2 * TileGeom<DH>::BYTES);  // lse * log2(e), +inf past the end
@@ -631,7 +675,7 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
 
   int kblk, e, j;  // the first key blocks see the most queries and start first
   if (!attn_map(blockIdx.x, (s + kBQ - 1) / kBQ, heads, b, &kblk, &e, &j)) return;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
+  const int wave = (threadIdx.x >> 6) & 1, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
   const int hp = heads * DH;
   const size_t rs = (size_t)b * 3 * hp;
   const bf16_t* base = qkv + (size_t)j * 3 * hp + (size_t)e * DH;
@@ -667,8 +711,8 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
     if constexpr (kPrefetch) {
       qmap.load(qr, base, rs, q0, s);
       domap.load(dor, dobase, dors, q0, s);
-      if (threadIdx.x < kBKV) {
-        const int q = q0 + threadIdx.x;
+      if (tid < kBKV) {
+        const int q = q0 + tid;
         lse_r = q < s ? lse_h[q] * 1.4426950408889634f : INFINITY;
         delta_r = q < s ? delta_h[q] : 0.f;
       }
@@ -678,39 +722,45 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
   if constexpr (kPrefetch) {
     qmap.init(rs);
     domap.init(dors);
-    fetch(qt_first * kBKV);
+    if (qt_first + pair < nq_tiles) fetch((qt_first + pair) * kBKV);
   }
-  for (int qt = qt_first; qt < nq_tiles; ++qt) {
+  // both pairs take the same number of steps (the barriers are the workgroup's); a pair without a tile idles
+  for (int qt0 = qt_first; qt0 < nq_tiles; qt0 += NP) {
+    const int qt = qt0 + pair;
+    const bool have = qt < nq_tiles;
     const int q0 = qt * kBKV;
     __syncthreads();
-    if constexpr (kPrefetch) {
-      qmap.store(qr, q_lds);
-      domap.store(dor, do_lds);
-      if (threadIdx.x < kBKV) {
-        lse_lds[threadIdx.x] = lse_r;
-        delta_lds[threadIdx.x] = delta_r;
+    if (have) {
+      if constexpr (kPrefetch) {
+        qmap.store(qr, q_lds);
+        domap.store(dor, do_lds);
+        if (tid < kBKV) {
+          lse_lds[tid] = lse_r;
+          delta_lds[tid] = delta_r;
+        }
+      } else {
+        TileRegs<DH> t;
+        t.load(base, rs, q0, s);
+        t.store(q_lds);
+        t.load(dobase, dors, q0, s);
+        t.store(do_lds);
+        if (tid < kBKV) {
+          const int q = q0 + tid;
+          lse_lds[tid] = q < s ? lse_h[q] * 1.4426950408889634f : INFINITY;
+          delta_lds[tid] = q < s ? delta_h[q] : 0.f;
+        }
       }
-    } else {
-      TileRegs<DH> t;
-      t.load(base, rs, q0, s);
-      t.store(q_lds);
-      t.load(dobase, dors, q0, s);
-      t.store(do_lds);
-      if (threadIdx.x < kBKV) {
-        const int q = q0 + threadIdx.x;
-        lse_lds[threadIdx.x] = q < s ? lse_h[q] * 1.4426950408889634f : INFINITY;
-        delta_lds[threadIdx.x] = q < s ? delta_h[q] : 0.f;
-      }
-    }
-    if (use_mask) {   // this tile of the mask, transposed to [key][query] so that a lane reads 4 queries at once
-      for (int idx = threadIdx.x; idx < kBKV * kBQ; idx += kAttnThreads) {
-        const int ql = idx / kBQ, kl = idx % kBQ;
-        const int q = q0 + ql, key = kblk * kBQ + kl;
-        mask_lds[kl * kMaskLdsStride + ql] = (q < s && key < s) ? mask[((size_t)j * s + q) * s + key] : (uint8_t)0;
+      if (use_mask) {   // this tile of the mask, transposed to [key][query] so that a lane reads 4 queries at once
+        for (int idx = tid; idx < kBKV * kBQ; idx += kAttnThreads) {
+          const int ql = idx / kBQ, kl = idx % kBQ;
+          const int q = q0 + ql, key = kblk * kBQ + kl;
+          mask_lds[kl * kMaskLdsStride + ql] = (q < s && key < s) ? mask[((size_t)j * s + q) * s + key] : (uint8_t)0;
+        }
       }
     }
     __syncthreads();
-    if (qt + 1 < nq_tiles) fetch(q0 + kBKV);
+    if (!have) continue;
+    if (qt + NP < nq_tiles) fetch(q0 + NP * kBKV);
     if (CAUSAL && q0 + kBKV - 1 < key_first) continue;  // every query of the tile precedes this wave's keys
     const bool diag = CAUSAL && q0 < key_first + 32;    // some query of the tile precedes some key of this wave
     bf16x8_t pf[2][2], dsf[2][2];
@@ -753,6 +803,29 @@ attn_bwd_dkv_mfma(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dct
           dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(do_lds, d, sub, ks, lane), pf[sub][ks], dv[d], 0, 0, 0);
           dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(q_lds, d, sub, ks, lane), dsf[sub][ks], dk[d], 0, 0, 0);
         }
+  }
+  if constexpr (NP == 2) {
+    // pair 1's sums join pair 0's: register r of lane l of wave w at sum[w][r][l]
+    __syncthreads();   // every wave is done with the tiles
+    float* sum = reinterpret_cast<float*>(smem_all) + wave * (2 * NDT * 16 * 64) + lane;
+    if (pair == 1) {
+#pragma unroll
+      for (int d = 0; d < NDT; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          sum[(d * 16 + r) * 64] = dk[d][r];
+          sum[((NDT + d) * 16 + r) * 64] = dv[d][r];
+        }
+    }
+    __syncthreads();
+    if (pair == 1) return;
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        dk[d][r] += sum[(d * 16 + r) * 64];
+        dv[d][r] += sum[((NDT + d) * 16 + r) * 64];
+      }
   }
   if (valid) {
     bf16_t* out = dqkv + (size_t)my_key * rs + (size_t)j * 3 * hp + (size_t)e * DH;
@@ -852,24 +925,42 @@ static int attn_bwd_rowwise_t(const void* qkv, const void* ctx, const float* lse
   return PTDP_OK;
 }
 
+// resident workgroups of the one-pair backward kernels: two per CU (one wave per SIMD each)
+static int attn_resident_pairs() {
+  int dev = 0, cu = 256;
+  if (hipGetDevice(&dev) == hipSuccess) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cu = v;
+  }
+  return 2 * cu;
+}
+template <int DH, bool CAUSAL, int NP>
+static int attn_bwd_mfma_np(const bf16_t* qkv, const bf16_t* dctx, const float* lse, const float* delta, bf16_t* dqkv, int s,
+                            int b, int heads, const uint8_t* mask, hipStream_t stream) {
+  constexpr int smem_dq = NP * 2 * TileGeom<DH>::BYTES;   // (NP = 2: the final sums, 2 x DH x 256 bytes, fit in the tiles)
+  constexpr int smem_dkv = NP == 2 ? DkvLds<DH, CAUSAL>::kBytes2 : DkvLds<DH, CAUSAL>::kPair;
+  static once_flag_t done_dq[kMaxDevices], done_dkv[kMaxDevices];
+  if (set_dynamic_smem(reinterpret_cast<const void*>(attn_bwd_dq_mfma<DH, CAUSAL, NP>), smem_dq, done_dq) != PTDP_OK ||
+      set_dynamic_smem(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH, CAUSAL, NP>), smem_dkv, done_dkv) != PTDP_OK)
+    return PTDP_E_HIP;
+  const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH, CAUSAL, NP>), grid, dim3(NP * kAttnThreads), smem_dkv, stream, qkv, dctx, lse, delta,
+                     dqkv, s, b, heads, mask);
+  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH, CAUSAL, NP>), grid, dim3(NP * kAttnThreads), smem_dq, stream, qkv, dctx, lse, delta,
+                     dqkv, s, b, heads, mask);
+  return PTDP_OK;
+}
 template <int DH, bool CAUSAL>
 static int attn_bwd_mfma_t(const bf16_t* qkv, const bf16_t* ctx, const float* lse, const bf16_t* dctx, bf16_t* dqkv,
                            float* delta, int s, int b, int heads, const uint8_t* mask, hipStream_t stream) {
-  constexpr int smem_dq = 2 * TileGeom<DH>::BYTES;
-  constexpr int smem_dkv = 2 * TileGeom<DH>::BYTES + 2 * kBKV * (int)sizeof(float) + (CAUSAL ? 0 : kBQ * kMaskLdsStride);
-  static once_flag_t done_dq[kMaxDevices], done_dkv[kMaxDevices];
-  if (set_dynamic_smem(reinterpret_cast<const void*>(attn_bwd_dq_mfma<DH, CAUSAL>), smem_dq, done_dq) != PTDP_OK ||
-      set_dynamic_smem(reinterpret_cast<const void*>(attn_bwd_dkv_mfma<DH, CAUSAL>), smem_dkv, done_dkv) != PTDP_OK)
-    return PTDP_E_HIP;
   const size_t nrows = (size_t)s * b * heads;
   hipLaunchKernelGGL(attn_delta_bf16, dim3((unsigned)((nrows + 3) / 4)), dim3(256), 0, stream, ctx, dctx, delta, s, b,
                      heads, DH);
-  const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
-  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH, CAUSAL>), grid, dim3(kAttnThreads), smem_dkv, stream, qkv, dctx, lse, delta, dqkv,
-                     s, b, heads, mask);
-  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH, CAUSAL>), grid, dim3(kAttnThreads), smem_dq, stream, qkv, dctx, lse, delta, dqkv, s,
-                     b, heads, mask);
-  return PTDP_OK;
+  // few workgroups: the longest one sets the time, so split its walk over two pairs of waves
+  const long long wgs = (long long)((s + kBQ - 1) / kBQ) * heads * b;
+  if (wgs <= attn_resident_pairs())
+    return attn_bwd_mfma_np<DH, CAUSAL, 2>(qkv, dctx, lse, delta, dqkv, s, b, heads, mask, stream);
+  return attn_bwd_mfma_np<DH, CAUSAL, 1>(qkv, dctx, lse, delta, dqkv, s, b, heads, mask, stream);
 }
 
 int launch_attn_bwd(int dtype, const void* qkv, const void* ctx, const float* lse, const void* dctx, void* dqkv,

@@ -92,7 +92,10 @@ def run_attn(dtype, s, b, heads, dh, seed=0, scale=1.0):
 ATTN_CASES = [(B.F32, 128, 2, 4, 64), (B.F32, 77, 1, 2, 32), (B.F32, 1, 2, 1, 64), (B.F32, 40, 1, 1, 160),
               (B.BF16, 128, 2, 2, 64), (B.BF16, 300, 2, 3, 128), (B.BF16, 333, 1, 2, 160), (B.BF16, 1, 1, 1, 128),
               (B.BF16, 64, 1, 1, 128), (B.BF16, 129, 1, 1, 64), (B.BF16, 520, 1, 1, 128),
-              (B.BF16, 200, 2, 3, 32), (B.BF16, 333, 1, 2, 96), (B.BF16, 65, 2, 1, 96)]
+              (B.BF16, 200, 2, 3, 32), (B.BF16, 333, 1, 2, 96), (B.BF16, 65, 2, 1, 96),
+              # more than 512 (query block, sample, head) triples: the backward kernels take their one-pair form
+              # (fewer: two pairs of waves per workgroup, as in every case above)
+              (B.BF16, 130, 8, 24, 32), (B.BF16, 200, 5, 27, 160), (B.BF16, 257, 3, 36, 128)]
 
 
 @pytest.mark.parametrize("dtype,s,b,heads,dh", ATTN_CASES)

@@ -32,6 +32,9 @@ CASES = [  # dtype, s, b, heads, dh, masked?, empty rows
     (B.BF16, 130, 1, 2, 96, False, []),
     (B.BF16, 64, 1, 1, 32, True, []),
     (B.BF16, 257, 1, 1, 128, True, [(0, 256)]),
+    # more than 512 (query block, sample, head) triples: one-pair form of the backward kernels
+    (B.BF16, 130, 6, 30, 64, True, [(2, 129)]),
+    (B.BF16, 140, 4, 44, 160, True, []),
 ]
 
 
