@@ -356,12 +356,17 @@ inline int attn_grid(int nblk, int heads, int b) { return 8 * ((heads * b + 7) /
 // vector ALU work, not by MFMA: the output is rescaled only when some row's running maximum moved,
 // the mask is applied only on tiles that touch the diagonal, and exponentials and bf16 conversions
 // are single instructions.
-template <int DH, bool CAUSAL>
-__global__ void __launch_bounds__(kAttnThreads, DH > 128 ? 1 : 2)
+// NP = 2: the workgroup is two pairs of waves; pair p walks every second key tile with tiles of its own in LDS, and
+// at the end pair 0 merges pair 1's running maximum, sum and output into its own (the usual rescaling of two
+// partial softmax results).  For launches with so few workgroups that the longest one sets the time.
+template <int DH, bool CAUSAL, int NP>
+__global__ void __launch_bounds__(NP * kAttnThreads, DH > 128 ? 1 : 2)
 attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* __restrict__ lse, int s, int b,
               int heads, const uint8_t* __restrict__ mask) {
   constexpr int NKK = DH / 16, NDT = DH / 32;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(16))) char smem_all[];
+  const int pair = NP == 2 ? threadIdx.x >> 7 : 0;
+  char* smem = smem_all + pair * 2 * TileGeom<DH>::BYTES;
   char* k_lds = smem;
   char* v_lds = smem + TileGeom<DH>::BYTES;
 
@@ -369,7 +374,7 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
   int qblk, e, j;
   if (!attn_map(blockIdx.x, nqb, heads, b, &qblk, &e, &j)) return;
   qblk = nqb - 1 - qblk;  // long rows first
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
+  const int wave = (threadIdx.x >> 6) & 1, lane = threadIdx.x & 63, half = lane >> 5, l31 = lane & 31;
   const int hp = heads * DH;
   const size_t rs = (size_t)b * 3 * hp;
   const bf16_t* base = qkv + (size_t)j * 3 * hp + (size_t)e * DH;
@@ -394,13 +399,18 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
   TileMap<DH> map;
   map.init(rs);
   TileRegs<DH> tr;
-  map.load(tr, base + hp, rs, 0, s);
-  map.store(tr, k_lds);
+  if (pair < ntiles) {
+    map.load(tr, base + hp, rs, pair * kBKV, s);
+    map.store(tr, k_lds);
+  }
   __syncthreads();
-  for (int kt = 0; kt < ntiles; ++kt) {
+  // both pairs take the same number of steps (the barriers are the workgroup's); a pair without a tile idles
+  for (int kt0 = 0; kt0 < ntiles; kt0 += NP) {
+    const int kt = kt0 + pair;
+    const bool have = kt < ntiles;
     const int key0 = kt * kBKV;
-    const bool active = !CAUSAL || key0 <= q_first + 31;  // else every key of the tile is in this wave's future
-    map.load(tr, base + 2 * hp, rs, key0, s);
+    const bool active = have && (!CAUSAL || key0 <= q_first + 31);  // else every key of the tile is in this wave's future
+    if (have) map.load(tr, base + 2 * hp, rs, key0, s);
     uint32_t mw[2][4];
     if (!CAUSAL && mrow) {
 #pragma unroll
@@ -476,9 +486,9 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
         pf[sub][1] = pack_frag(sacc[sub], 1);
       }
     }
-    map.store(tr, v_lds);
+    if (have) map.store(tr, v_lds);
     __syncthreads();   // V visible; every wave is done with K of this step
-    if (kt + 1 < ntiles) map.load(tr, base + hp, rs, key0 + kBKV, s);
+    if (kt + NP < ntiles) map.load(tr, base + hp, rs, key0 + NP * kBKV, s);
     if (active) {
 #pragma unroll
       for (int d = 0; d < NDT; ++d)
@@ -488,10 +498,33 @@ attn_fwd_mfma(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ ctx, float* _
           for (int ks = 0; ks < 2; ++ks)
             o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr<DH>(v_lds, d, sub, ks, lane), pf[sub][ks], o[d], 0, 0, 0);
     }
-    if (kt + 1 < ntiles) map.store(tr, k_lds);
+    if (kt + NP < ntiles) map.store(tr, k_lds);
     __syncthreads();   // next K visible; every wave is done with V of this step
   }
   l_run += __shfl_xor(l_run, 32, 64);
+  if constexpr (NP == 2) {
+    // pair 1's partial result joins pair 0's: value v of lane l of wave w at part[w][v][l]
+    float* part = reinterpret_cast<float*>(smem_all) + wave * ((2 + NDT * 16) * 64) + lane;
+    if (pair == 1) {
+      part[0] = m_run;
+      part[64] = l_run;
+#pragma unroll
+      for (int d = 0; d < NDT; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) part[(2 + d * 16 + r) * 64] = o[d][r];
+    }
+    __syncthreads();
+    if (pair == 1) return;
+    const float m1 = part[0], l1 = part[64];
+    const float m = fmaxf(m_run, m1);   // pair 0 always has tile 0, whose key 0 every query sees: m_run is finite
+    const float a0 = __builtin_amdgcn_exp2f((m_run - m) * c2), a1 = __builtin_amdgcn_exp2f((m1 - m) * c2);
+    l_run = l_run * a0 + l1 * a1;
+    m_run = m;
+#pragma unroll
+    for (int d = 0; d < NDT; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] = o[d][r] * a0 + part[(2 + d * 16 + r) * 64] * a1;
+  }
   if (my_q < s) {
     store_cols<NDT>(ctx + ((size_t)my_q * b + j) * hp + (size_t)e * DH, o, 1.f / l_run, half);
     if (half == 0) lse[((size_t)j * heads + e) * s + my_q] = m_run * rsqrtf((float)DH) + __logf(l_run);
@@ -873,15 +906,33 @@ bool attn_dh_supported(int dtype, int dh) {
 
 static inline double attn_flops(int s, int b, int heads, int dh) { return 4.0 * b * heads * (double)s * s * dh; }
 
+// resident workgroups of the one-pair kernels: two per CU (one wave per SIMD each)
+static int attn_resident_pairs() {
+  int dev = 0, cu = 256;
+  if (hipGetDevice(&dev) == hipSuccess) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cu = v;
+  }
+  return 2 * cu;
+}
+template <int DH, bool CAUSAL, int NP>
+static int attn_fwd_mfma_np(const bf16_t* qkv, bf16_t* ctx, float* lse, int s, int b, int heads, const uint8_t* mask,
+                            hipStream_t stream) {
+  constexpr int smem = NP * 2 * TileGeom<DH>::BYTES;   // (NP = 2: the partial results, (2 + DH / 2) x 512 bytes, fit in the tiles)
+  static once_flag_t done[kMaxDevices];
+  if (set_dynamic_smem(reinterpret_cast<const void*>(attn_fwd_mfma<DH, CAUSAL, NP>), smem, done) != PTDP_OK) return PTDP_E_HIP;
+  const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
+  hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL, NP>), grid, dim3(NP * kAttnThreads), smem, stream, qkv, ctx, lse, s, b, heads,
+                     mask);
+  return PTDP_OK;
+}
 template <int DH, bool CAUSAL>
 static int attn_fwd_mfma_t(const bf16_t* qkv, bf16_t* ctx, float* lse, int s, int b, int heads, const uint8_t* mask,
                            hipStream_t stream) {
-  constexpr int smem = 2 * TileGeom<DH>::BYTES;
-  static once_flag_t done[kMaxDevices];
-  if (set_dynamic_smem(reinterpret_cast<const void*>(attn_fwd_mfma<DH, CAUSAL>), smem, done) != PTDP_OK) return PTDP_E_HIP;
-  const dim3 grid(attn_grid((s + kBQ - 1) / kBQ, heads, b));
-  hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL>), grid, dim3(kAttnThreads), smem, stream, qkv, ctx, lse, s, b, heads, mask);
-  return PTDP_OK;
+  // few workgroups: the longest one sets the time, so split its walk over two pairs of waves
+  const long long wgs = (long long)((s + kBQ - 1) / kBQ) * heads * b;
+  if (wgs <= attn_resident_pairs()) return attn_fwd_mfma_np<DH, CAUSAL, 2>(qkv, ctx, lse, s, b, heads, mask, stream);
+  return attn_fwd_mfma_np<DH, CAUSAL, 1>(qkv, ctx, lse, s, b, heads, mask, stream);
 }
 
 // Without the causal mask every row is a full row: count the whole s x s square as executed too.
@@ -925,15 +976,6 @@ static int attn_bwd_rowwise_t(const void* qkv, const void* ctx, const float* lse
   return PTDP_OK;
 }
 
-// resident workgroups of the one-pair backward kernels: two per CU (one wave per SIMD each)
-static int attn_resident_pairs() {
-  int dev = 0, cu = 256;
-  if (hipGetDevice(&dev) == hipSuccess) {
-    int v = 0;
-    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cu = v;
-  }
-  return 2 * cu;
-}
 template <int DH, bool CAUSAL, int NP>
 static int attn_bwd_mfma_np(const bf16_t* qkv, const bf16_t* dctx, const float* lse, const float* delta, bf16_t* dqkv, int s,
                             int b, int heads, const uint8_t* mask, hipStream_t stream) {
