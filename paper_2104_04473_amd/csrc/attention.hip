@@ -908,11 +908,15 @@ static inline double attn_flops(int s, int b, int heads, int dh) { return 4.0 * 
 
 // resident workgroups of the one-pair kernels: two per CU (one wave per SIMD each)
 static int attn_resident_pairs() {
+  static std::atomic<int> cached[kMaxDevices];   // per device, looked up once
+  const int d = device_slot();
+  if (d >= 0 && cached[d].load(std::memory_order_relaxed) > 0) return cached[d].load(std::memory_order_relaxed);
   int dev = 0, cu = 256;
   if (hipGetDevice(&dev) == hipSuccess) {
     int v = 0;
     if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cu = v;
   }
+  if (d >= 0) cached[d].store(2 * cu, std::memory_order_relaxed);
   return 2 * cu;
 }
 template <int DH, bool CAUSAL, int NP>
