@@ -38,6 +38,33 @@ def test_gemm(dtype, mode, M, N, K):
 
 
 @pytest.mark.parametrize("mode", [B.GEMM_NN, B.GEMM_NT, B.GEMM_TN])
+@pytest.mark.parametrize("K,Kpad", [(192, 256), (200, 256), (4096, 4104), (520, 576)])
+def test_gemm_zero_padding_along_k_changes_no_bit(mode, K, Kpad):
+    """The same product with the reduction index padded by zeros.  K = 192 -> 256 moves a k-contiguous operand from
+    rows shorter than 256 elements (every operand request in the general form, with per-lane checks) to rows of 256
+    (whole k-tiles requested in the lean form); 4096 -> 4104 and 520 -> 576 add or remove a partial last k-tile.
+    Every output element adds the same products in the same order plus exact zeros: the results agree bit for bit."""
+    M, N = 520, 264
+    a = randn((M, K), B.BF16, 1)
+    b = randn((K, N), B.BF16, 2)
+    ap = torch.zeros((M, Kpad), dtype=torch.bfloat16, device="cuda"); ap[:, :K] = a
+    bp = torch.zeros((Kpad, N), dtype=torch.bfloat16, device="cuda"); bp[:K] = b
+    outs = []
+    for (x, y, k) in ((a, b, K), (ap, bp, Kpad)):
+        A = x.t().contiguous() if mode == B.GEMM_TN else x.contiguous()
+        Bm = y.t().contiguous() if mode == B.GEMM_NT else y.contiguous()
+        c = torch.full((M, N), 9.0, dtype=torch.bfloat16, device="cuda")
+        acc = torch.full((M, N), 0.25, dtype=torch.float32, device="cuda")
+        B.check(B.ptdp_gemm(B.BF16, mode, A.data_ptr(), Bm.data_ptr(), c.data_ptr(), None, M, N, k, 0, 0, None, 0, stream()), "gemm")
+        B.check(B.ptdp_gemm(B.BF16, mode, A.data_ptr(), Bm.data_ptr(), acc.data_ptr(), None, M, N, k, 1, 1, None, 0, stream()), "gemm")
+        sync()
+        outs.append((c, acc))
+    assert torch.equal(outs[0][0], outs[1][0])
+    assert torch.equal(outs[0][1], outs[1][1])
+    assert_close(np64(outs[0][1]) - 0.25, np64(a) @ np64(b), B.BF16, "C +=")
+
+
+@pytest.mark.parametrize("mode", [B.GEMM_NN, B.GEMM_NT, B.GEMM_TN])
 @pytest.mark.parametrize("M,N,K", [(520, 776, 4168), (264, 4104, 4096), (2048, 1288, 4160), (2048, 10248, 4096),
                                    (14336, 1792, 4096)])   # 56 row tiles: do not divide the compute-unit count
 def test_gemm_split_along_k(mode, M, N, K):
