@@ -385,13 +385,20 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kB
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bfr[c][j], acc[i][j], 0, 0, 0);
       // Scheduling hint: spread this step's LDS reads between its MFMAs instead of ahead of them (measured:
       // +2..5 % with two 16-byte reads per two MFMAs when both operands are k-contiguous, +1 % one to one
-      // when B needs transposing reads, nothing when both do).
+      // when B needs transposing reads; when both do - the weight gradients, 24 eight-byte reads for 8 MFMAs -
+      // three reads after every MFMA: +1.5..2 % at the 1T-shaped layer's shapes, +4 % at w_o's).
       if (!TA) {
         constexpr int per = TB ? 1 : 2;
 #pragma unroll
         for (int q = 0; q < TM * TN / per; ++q) {
           __builtin_amdgcn_sched_group_barrier(0x008, per, 0);   // MFMA
           __builtin_amdgcn_sched_group_barrier(0x100, per, 0);   // LDS read
+        }
+      } else {
+#pragma unroll
+        for (int q = 0; q < TM * TN; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // LDS reads
         }
       }
     }
@@ -560,11 +567,13 @@ __device__ __forceinline__ void gemm_mainloop16(f32x4_t (&acc)[kBM / WGM / 16][k
         for (int j = 0; j < CB; ++j)
           acc[half * HB + i][j] =
               __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[p & 1][i], bfr[ks & 1][j], acc[half * HB + i][j], 0, 0, 0);
-      // Scheduling hint: spread this phase's LDS reads between its MFMAs instead of ahead of them
+      // Scheduling hint: spread this phase's LDS reads (4 to 12, for 16 MFMAs) between its MFMAs instead of ahead
+      // of them, one after each (measured against one after every two: +2..3 % forward, +5 % at K = 3200,
+      // +1.5..2.5 % data gradients)
       if (!TA) {
 #pragma unroll
-        for (int q = 0; q < HB * CB / 2; ++q) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // MFMA
+        for (int q = 0; q < HB * CB; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
         }
       }
