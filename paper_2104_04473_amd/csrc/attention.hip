@@ -337,17 +337,31 @@ __device__ __forceinline__ uint32_t mask_word(const uint8_t* __restrict__ mrow, 
 
 // Work assignment.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: every block of one
 // (sample, head) pair goes to the same XCD so that the pair's K and V stay in that L2, and each XCD
-// takes its pairs one after the other.  Returns false for surplus ids.  `blk` counts up within a pair.
+// takes its pairs one after the other - as long as whole rounds of 8 pairs remain.  The last heads * b mod 8 pairs
+// are dealt block by block instead (block-major, so that each XCD gets the same share of every block index and
+// with it of the causal triangle's work): 20 heads would otherwise leave four XCDs with three pairs and four
+// with two.  Returns false for surplus ids.  `blk` counts up within a pair.
 __device__ __forceinline__ bool attn_map(int id, int nblk, int heads, int b, int* blk, int* e, int* j) {
   const int xcd = id & 7, local = id >> 3;
-  const int pair = xcd + 8 * (local / nblk);
-  if (pair >= heads * b) return false;
-  *blk = local % nblk;
+  const int pairs = heads * b, whole = pairs >> 3, rest = pairs & 7;
+  int pair;
+  if (local < whole * nblk) {
+    pair = xcd + 8 * (local / nblk);
+    *blk = local % nblk;
+  } else {
+    const int g = (local - whole * nblk) * 8 + xcd;   // index into the remaining pairs' blocks, block-major
+    if (g >= rest * nblk) return false;
+    pair = 8 * whole + g % rest;
+    *blk = g / rest;
+  }
   *e = pair % heads;
   *j = pair / heads;
   return true;
 }
-inline int attn_grid(int nblk, int heads, int b) { return 8 * ((heads * b + 7) / 8) * nblk; }
+inline int attn_grid(int nblk, int heads, int b) {
+  const int pairs = heads * b, whole = pairs >> 3, rest = pairs & 7;
+  return 8 * (whole * nblk + (rest * nblk + 7) / 8);
+}
 
 // Forward: S^T = K Q^T and O^T = V^T P^T, so that the probabilities leave the first MFMA in the register
 // layout the second one takes as its B operand.  One tile's worth of registers carries V of the
