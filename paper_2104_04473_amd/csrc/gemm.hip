@@ -385,8 +385,9 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kB
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bfr[c][j], acc[i][j], 0, 0, 0);
       // Scheduling hint: spread this step's LDS reads between its MFMAs instead of ahead of them (measured:
       // +2..5 % with two 16-byte reads per two MFMAs when both operands are k-contiguous, +1 % one to one
-      // when B needs transposing reads; when both do - the weight gradients, 24 eight-byte reads for 8 MFMAs -
-      // three reads after every MFMA: +1.5..2 % at the 1T-shaped layer's shapes, +4 % at w_o's).
+      // when B needs transposing reads; when both do - the weight gradients, 12 eight-byte reads for 8 MFMAs -
+      // three reads after each of the first four MFMAs: +1.5..2 % at the 1T-shaped layer's shapes, +4 % at w_o's;
+      // two after each is slower, four the same, six or all twelve up front slower again).
       if (!TA) {
         constexpr int per = TB ? 1 : 2;
 #pragma unroll
