@@ -8,6 +8,29 @@ namespace ptdp {
 
 static constexpr int kColRows = 32;  // rows per block in the column-sum producers
 
+// The column-sum producers (bias+GeLU backward, bias+dropout+add backward, plain column sums) run 256-thread
+// workgroups of 64 column groups (16 bytes each) x 4 row lanes: wave w takes rows r0 + w, r0 + w + 4, ... of
+// the block's kColRows rows, a whole 1 KiB run of one row per access, eight rows per thread in flight, and
+// width / 512 x rows / 32 workgroups per launch (one thread walking all 32 rows left a 6144-wide bf16 gradient
+// with 192 workgroups for 256 CUs).  The four waves' sums meet in LDS and wave 0 adds them in a fixed order.
+static constexpr int kColLanes = 4;
+static inline dim3 colsum_grid(int nvec, int rows) { return dim3((nvec + 63) / 64, (rows + kColRows - 1) / kColRows); }
+template <int N>
+__device__ __forceinline__ void colsum_block_store(float (&acc)[N], float* __restrict__ part, int width, int c, bool valid) {
+  __shared__ float red[kColLanes - 1][N][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (w > 0) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) red[w - 1][j][lane] = acc[j];
+  }
+  __syncthreads();
+  if (w == 0 && valid) {
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+      part[(size_t)blockIdx.y * width + (size_t)c * N + j] = (acc[j] + red[0][j][lane]) + (red[1][j][lane] + red[2][j][lane]);
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // LayerNorm forward: one block per row, the row lives in registers (VPT 16-byte vectors per thread).
 // ------------------------------------------------------------------------------------------------
@@ -257,19 +280,28 @@ colsum_finish_batch_kernel(ColsumBatchArgs a) {
 // ------------------------------------------------------------------------------------------------
 // Standard normal CDF Phi(z) and density phi(z) from one exponential: with x = |z| / sqrt(2),
 // erfc(x) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-x^2), t = 1 / (1 + p x) (Abramowitz & Stegun 7.1.26,
-// absolute error below 1.5e-7), taken on the side that needs no cancellation.
+// absolute error below 1.5e-7), taken on the side that needs no cancellation.  These kernels are bound by their
+// arithmetic, not by memory (41 vector instructions per element before, against 16 bytes moved per 8 elements), so
+// the constants are folded (the coefficients carry erfc's factor 0.5, the exponent -log2(e)/2) and the reciprocal is
+// the hardware's 1-ulp one instead of a correctly rounded division (ten instructions): its error is a tenth of the
+// formula's own.
 __device__ __forceinline__ float normal_cdf_pdf(float z, float* pdf) {
-  const float e = __expf(-0.5f * z * z);
-  const float t = __frcp_rn(1.f + 0.3275911f * 0.7071067811865476f * fabsf(z));
-  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-  const float tail = 0.5f * poly * e;   // 0.5 erfc(|z| / sqrt(2))
+  const float e = __builtin_amdgcn_exp2f(z * z * -0.7213475204444817f);   // exp(-z^2 / 2)
+  const float t = __builtin_amdgcn_rcpf(fmaf(fabsf(z), 0.3275911f * 0.7071067811865476f, 1.f));
+  const float poly = t * (0.127414796f + t * (-0.142248368f + t * (0.7107068705f + t * (-0.7265760135f + t * 0.5307027145f))));
+  const float tail = poly * e;   // 0.5 erfc(|z| / sqrt(2))
   *pdf = e * 0.3989422804014327f;
   return z < 0.f ? tail : 1.f - tail;
+}
+// tanh(u) = 1 - 2 / (1 + exp(2u)) with the hardware's exponential and reciprocal (absolute error ~1e-7; exp
+// overflowing to infinity gives exactly 1, underflowing to zero exactly -1)
+__device__ __forceinline__ float fast_tanh(float u) {
+  return 1.f - 2.f * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(u * 2.8853900817779268f));
 }
 template <int MODE> __device__ __forceinline__ float gelu_f(float z) {
   if (MODE == PTDP_GELU_TANH) {
     const float c = 0.7978845608028654f;
-    return 0.5f * z * (1.f + tanhf(c * (z + 0.044715f * z * z * z)));
+    return 0.5f * z * (1.f + fast_tanh(c * (z + 0.044715f * z * z * z)));
   }
   float pdf;
   return z * normal_cdf_pdf(z, &pdf);
@@ -277,7 +309,7 @@ template <int MODE> __device__ __forceinline__ float gelu_f(float z) {
 template <int MODE> __device__ __forceinline__ float gelu_grad_f(float z) {
   if (MODE == PTDP_GELU_TANH) {
     const float c = 0.7978845608028654f;
-    const float th = tanhf(c * (z + 0.044715f * z * z * z));
+    const float th = fast_tanh(c * (z + 0.044715f * z * z * z));
     return 0.5f * (1.f + th) + 0.5f * z * (1.f - th * th) * c * (1.f + 3.f * 0.044715f * z * z);
   }
   float pdf;
@@ -303,39 +335,41 @@ __global__ void bias_gelu_fwd_kernel(const T* __restrict__ z, const T* __restric
   }
 }
 
-// grid (column slabs, row tiles of kColRows); thread owns one 16-byte column group.
+// grid (slabs of 64 column groups, row tiles of kColRows); thread owns one 16-byte column group of every fourth row.
 template <typename T, int MODE>
-__global__ void bias_gelu_bwd_kernel(const T* dg, const T* __restrict__ z, const T* __restrict__ bias, T* dz,
-                                     float* __restrict__ part, int rows, int width) {
+__global__ void __launch_bounds__(256)
+bias_gelu_bwd_kernel(const T* dg, const T* __restrict__ z, const T* __restrict__ bias, T* dz,
+                     float* __restrict__ part, int rows, int width) {
   constexpr int N = Vec16<T>::N;
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= width / N) return;
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const bool valid = c < width / N;
   float bf[N], acc[N];
-  Vec16<T> b;
-  b.load(bias + (size_t)c * N);
-  b.unpack(bf);
 #pragma unroll
   for (int j = 0; j < N; ++j) acc[j] = 0.f;
-  const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
-#pragma unroll 4
-  for (int r = r0; r < r1; ++r) {
-    const size_t off = (size_t)r * width + (size_t)c * N;
-    Vec16<T> a, zz;
-    float af[N], zf[N];
-    a.load(dg + off);
-    zz.load(z + off);
-    a.unpack(af);
-    zz.unpack(zf);
+  if (valid) {
+    Vec16<T> b;
+    b.load(bias + (size_t)c * N);
+    b.unpack(bf);
+    const int r0 = blockIdx.y * kColRows + (threadIdx.x >> 6), r1 = min(rows, (int)(blockIdx.y + 1) * kColRows);
+#pragma unroll 8
+    for (int r = r0; r < r1; r += kColLanes) {
+      const size_t off = (size_t)r * width + (size_t)c * N;
+      Vec16<T> a, zz;
+      float af[N], zf[N];
+      a.load(dg + off);
+      zz.load(z + off);
+      a.unpack(af);
+      zz.unpack(zf);
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-      af[j] *= gelu_grad_f<MODE>(zf[j] + bf[j]);
-      acc[j] += af[j];
+      for (int j = 0; j < N; ++j) {
+        af[j] *= gelu_grad_f<MODE>(zf[j] + bf[j]);
+        acc[j] += af[j];
+      }
+      a.pack(af);
+      a.store(dz + off);
     }
-    a.pack(af);
-    a.store(dz + off);
   }
-#pragma unroll
-  for (int j = 0; j < N; ++j) part[(size_t)blockIdx.y * width + (size_t)c * N + j] = acc[j];
+  colsum_block_store<N>(acc, part, width, c, valid);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -366,58 +400,62 @@ __global__ void bda_fwd_kernel(const T* __restrict__ in, const T* __restrict__ b
 }
 
 template <typename T>
-__global__ void bda_bwd_kernel(const T* __restrict__ dout, T* __restrict__ din, float* __restrict__ part, int rows,
-                               int width, uint64_t key, uint32_t thr, float scale) {
+__global__ void __launch_bounds__(256)
+bda_bwd_kernel(const T* __restrict__ dout, T* __restrict__ din, float* __restrict__ part, int rows,
+               int width, uint64_t key, uint32_t thr, float scale) {
   constexpr int N = Vec16<T>::N;
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= width / N) return;
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const bool valid = c < width / N;
   float acc[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) acc[j] = 0.f;
-  const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
-#pragma unroll 4
-  for (int r = r0; r < r1; ++r) {
-    const size_t off = (size_t)r * width + (size_t)c * N;
-    Vec16<T> a;
-    float af[N];
-    bool keep[N];
-    a.load(dout + off);
-    a.unpack(af);
-    keep_flags<N>(key, (uint64_t)off, thr, keep);
+  if (valid) {
+    const int r0 = blockIdx.y * kColRows + (threadIdx.x >> 6), r1 = min(rows, (int)(blockIdx.y + 1) * kColRows);
+#pragma unroll 8
+    for (int r = r0; r < r1; r += kColLanes) {
+      const size_t off = (size_t)r * width + (size_t)c * N;
+      Vec16<T> a;
+      float af[N];
+      bool keep[N];
+      a.load(dout + off);
+      a.unpack(af);
+      keep_flags<N>(key, (uint64_t)off, thr, keep);
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-      af[j] = keep[j] ? af[j] * scale : 0.f;
-      acc[j] += af[j];
+      for (int j = 0; j < N; ++j) {
+        af[j] = keep[j] ? af[j] * scale : 0.f;
+        acc[j] += af[j];
+      }
+      a.pack(af);
+      a.store(din + off);
     }
-    a.pack(af);
-    a.store(din + off);
   }
-#pragma unroll
-  for (int j = 0; j < N; ++j) part[(size_t)blockIdx.y * width + (size_t)c * N + j] = acc[j];
+  colsum_block_store<N>(acc, part, width, c, valid);
 }
 
 // part[blockIdx.y][c] = sum of in[r][c] over the block's kColRows rows (first stage of a bias gradient
 // whose producer lives in another kernel, e.g. the QKV bias).
 template <typename T>
-__global__ void colsum_rows_kernel(const T* __restrict__ in, float* __restrict__ part, int rows, int width) {
+__global__ void __launch_bounds__(256)
+colsum_rows_kernel(const T* __restrict__ in, float* __restrict__ part, int rows, int width) {
   constexpr int N = Vec16<T>::N;
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= width / N) return;
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const bool valid = c < width / N;
   float acc[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) acc[j] = 0.f;
-  const int r0 = blockIdx.y * kColRows, r1 = min(rows, r0 + kColRows);
-#pragma unroll 4
-  for (int r = r0; r < r1; ++r) {
-    Vec16<T> a;
-    float af[N];
-    a.load(in + (size_t)r * width + (size_t)c * N);
-    a.unpack(af);
+  if (valid) {
+    const int r0 = blockIdx.y * kColRows + (threadIdx.x >> 6), r1 = min(rows, (int)(blockIdx.y + 1) * kColRows);
+#pragma unroll 8
+    for (int r = r0; r < r1; r += kColLanes) {
+      Vec16<T> a;
+      float af[N];
+      a.load(in + (size_t)r * width + (size_t)c * N);
+      a.unpack(af);
 #pragma unroll
-    for (int j = 0; j < N; ++j) acc[j] += af[j];
+      for (int j = 0; j < N; ++j) acc[j] += af[j];
+    }
   }
-#pragma unroll
-  for (int j = 0; j < N; ++j) part[(size_t)blockIdx.y * width + (size_t)c * N + j] = acc[j];
+  colsum_block_store<N>(acc, part, width, c, valid);
 }
 
 __global__ void dropout_mask_kernel(uint8_t* keep, int64_t n, uint64_t key, uint32_t thr) {
@@ -562,7 +600,7 @@ int launch_layernorm_bwd(int dtype, const void* du, const void* x, const void* g
 
 static inline int stream_grid(size_t total_vec) {
   size_t blocks = (total_vec + 255) / 256;
-  const size_t cap = 256 * 16;  // 16 blocks per CU, grid-stride beyond
+  const size_t cap = 256 * 32;  // 32 blocks per CU, grid-stride beyond (16: bias+dropout+add 4-5 % slower; 64 and more: the same)
   return (int)(blocks < cap ? (blocks ? blocks : 1) : cap);
 }
 
@@ -591,8 +629,7 @@ template <typename T>
 static int gelu_bwd_t(int mode, const void* dg, const void* z, const void* bias, void* dz, float* dbias,
                       void* scratch, int rows, int width, hipStream_t st, ColsumBatch* defer) {
   constexpr int N = Vec16<T>::N;
-  const int nvec = width / N;
-  const dim3 grid((nvec + 255) / 256, (rows + kColRows - 1) / kColRows);
+  const dim3 grid = colsum_grid(width / N, rows);
   float* part = (float*)scratch;
   {
     Launch L(PTDP_K_GELU_BWD, (double)rows * width * sizeof(T) * 3, st);
@@ -637,8 +674,7 @@ template <typename T>
 static int bda_bwd_t(const void* dout, void* din, float* dbias, void* scratch, int rows, int width, float p,
                      uint64_t key, hipStream_t st, ColsumBatch* defer) {
   constexpr int N = Vec16<T>::N;
-  const int nvec = width / N;
-  const dim3 grid((nvec + 255) / 256, (rows + kColRows - 1) / kColRows);
+  const dim3 grid = colsum_grid(width / N, rows);
   float* part = (float*)scratch;
   {
     Launch L(PTDP_K_BDA_BWD, (double)rows * width * sizeof(T) * 2, st);
@@ -689,7 +725,7 @@ int launch_bda_bwd_static(int dtype, const void* dout, void* din, float* dbias, 
 template <typename T>
 static int colsum_t(const void* in, float* out, void* scratch, int rows, int width, hipStream_t st, ColsumBatch* defer) {
   constexpr int N = Vec16<T>::N;
-  const dim3 grid((width / N + 255) / 256, (rows + kColRows - 1) / kColRows);
+  const dim3 grid = colsum_grid(width / N, rows);
   float* part = (float*)scratch;
   {
     Launch L(PTDP_K_COLSUM, (double)rows * width * sizeof(T), st);

@@ -1,6 +1,6 @@
 """Each exported kernel alone at the shapes of a workload, against its roofline.
 
-    python -m paper_2104_04473_amd.kernel_bench [--shape c4|c3|c2] [--iters 10]
+    python -m paper_2104_04473_amd.kernel_bench [--shape c4|c3|c2] [--iters 10] [--only elementwise]
 
 Element-wise kernels rotate over enough distinct buffers (> 512 MB in total) that the 256 MB memory-side
 cache cannot serve them; GEMMs and attention run on one buffer set (their operands exceed the caches or
@@ -21,6 +21,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--shape", default="c4", choices=sorted(SHAPES))
     ap.add_argument("--iters", type=int, default=10)
+    ap.add_argument("--only", default="all", choices=["all", "elementwise"])
     args = ap.parse_args()
     import torch
     from . import binding as B
@@ -98,6 +99,8 @@ def main():
            [lambda i=i: B.ptdp_bias_gelu_bwd(B.BF16, B.GELU_ERF, gs[i].data_ptr(), zs[i].data_ptr(), b1.data_ptr(),
                                              gs[i].data_ptr(), db1.data_ptr(), scratch.data_ptr(), T, fp, sh) for i in range(n)])
     del zs, gs
+    if args.only == "elementwise":
+        return
 
     # ---- GEMMs of one layer ----------------------------------------------------------------------------
     ws = torch.empty(B.ptdp_gemm_workspace_bytes(), dtype=torch.uint8, device=dev)
