@@ -346,7 +346,6 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kB
 #pragma unroll
   for (int j = 0; j < TN; ++j) bfr[0][j] = read_frag<TB>(smem + kTileBytes, wn0 + j * 32, 0, lane);
 
-  constexpr bool kIssueBeforeReads = !TA && !TB;
   auto request = [&](char* stage, int kt) {
     __builtin_amdgcn_s_setprio(1);
     la.issue(ra, stage, wave, lane, kt, kend);
@@ -370,13 +369,14 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[kBM / WGM / 32][kB
         // every fragment of `cur` is in registers: the next tile may be consumed, `cur` may be refilled
         wait_vmcnt0();
         __syncthreads();
-        // (nothing is requested past the last tile: no load may be in flight when the epilogue reuses LDS)
-        if (kIssueBeforeReads && kt + 2 < kt1) request(cur, kt + 2);
 #pragma unroll
         for (int i = 0; i < TM; ++i) af[n][i] = read_frag<TA>(nxt, wm0 + i * 32, 0, lane);
 #pragma unroll
         for (int j = 0; j < TN; ++j) bfr[n][j] = read_frag<TB>(nxt + kTileBytes, wn0 + j * 32, 0, lane);
-        if (!kIssueBeforeReads && kt + 2 < kt1) request(cur, kt + 2);
+        // the refill goes out after the next tile's first fragment reads (ahead of them: data gradients 1-2 % slower,
+        // the others the same); nothing is requested past the last tile: no load may be in flight when the epilogue
+        // reuses LDS
+        if (kt + 2 < kt1) request(cur, kt + 2);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -527,7 +527,6 @@ __device__ __forceinline__ void gemm_mainloop16(f32x4_t (&acc)[kBM / WGM / 16][k
 #pragma unroll
   for (int j = 0; j < CB; ++j) bfr[0][j] = read_frag16<TB>(smem + kTileBytes, wn0 + j * 16, 0, lane);
 
-  constexpr bool kIssueBeforeReads = !TA && !TB;
   auto request = [&](char* stage, int kt) {
     __builtin_amdgcn_s_setprio(1);
     la.issue(ra, stage, wave, lane, kt, kend);
@@ -554,13 +553,14 @@ __device__ __forceinline__ void gemm_mainloop16(f32x4_t (&acc)[kBM / WGM / 16][k
         // every fragment of `cur` is in registers: the next tile may be consumed, `cur` may be refilled
         wait_vmcnt0();
         __syncthreads();
-        // (nothing is requested past the last tile: no load may be in flight when the epilogue reuses LDS)
-        if (kIssueBeforeReads && kt + 2 < kt1) request(cur, kt + 2);
 #pragma unroll
         for (int i = 0; i < HB; ++i) af[0][i] = read_frag16<TA>(nxt, wm0 + i * 16, 0, lane);
 #pragma unroll
         for (int j = 0; j < CB; ++j) bfr[0][j] = read_frag16<TB>(nxt + kTileBytes, wn0 + j * 16, 0, lane);
-        if (!kIssueBeforeReads && kt + 2 < kt1) request(cur, kt + 2);
+        // the refill goes out after the next tile's first fragment reads (ahead of them: data gradients 1-2 % slower,
+        // the others the same); nothing is requested past the last tile: no load may be in flight when the epilogue
+        // reuses LDS
+        if (kt + 2 < kt1) request(cur, kt + 2);
       }
 #pragma unroll
       for (int i = 0; i < HB; ++i)
