@@ -11,6 +11,7 @@
 // transposing LDS reads.
 // fp32 path: a plain LDS-tiled FMA kernel (correctness configuration only).
 #include "common.h"
+#include <type_traits>
 
 namespace ptdp {
 
@@ -122,6 +123,14 @@ __device__ __forceinline__ void load_lds_16x4(rsrc_t r, char* dst, uint32_t v0, 
                "buffer_load_dwordx4 %4, %5, %6 offen offset:3072 lds"
                :: "s"(lds_offset(dst)), "v"(v0), "v"(v1), "v"(v2), "v"(v3), "s"(r), "s"(soff) : "memory", "m0");
 }
+// two of the four: loads H*2 and H*2+1 of a group (instruction offsets 2048*H and 2048*H + 1024)
+template <int H>
+__device__ __forceinline__ void load_lds_16x2(rsrc_t r, char* dst, uint32_t v0, uint32_t v1, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\t"
+               "buffer_load_dwordx4 %1, %3, %4 offen offset:%5 lds\n\t"
+               "buffer_load_dwordx4 %2, %3, %4 offen offset:%6 lds"
+               :: "s"(lds_offset(dst)), "v"(v0), "v"(v1), "s"(r), "s"(soff), "n"(H * 2048), "n"(H * 2048 + 1024) : "memory", "m0");
+}
 
 // One 256-row operand tile of 64 k (32 KiB) is filled by 32 wave-loads of 1 KiB; wave w of NW issues
 // wave-loads w*LPW .. w*LPW+LPW-1.
@@ -163,6 +172,15 @@ template <bool KSLOW, int NW> struct TileLoad {
     if (KSLOW) return kfirst + 2 * i;
     const int row = (wave * LPW + i) * 8 + (lane >> 3);
     return ((lane & 7) ^ ((row >> 1) & 7)) * 8;
+  }
+  // The same request in two instalments (four loads per wave only): H = 0 issues loads 0 and 1, H = 1 loads 2 and 3;
+  // where the lean form does not apply, H = 0 issues everything and H = 1 nothing.
+  template <int H> __device__ __forceinline__ void issue_half(rsrc_t r, char* tile, int wave, int lane, int kt, int K) {
+    static_assert(LPW == 4, "one group of four loads per wave");
+    if (plain && (kt + 1) * BK <= K)
+      load_lds_16x2<H>(r, tile + wave * LPW * 1024, offm[2 * H], offm[2 * H + 1], (uint32_t)kt * kstep);
+    else if (H == 0)
+      issue(r, tile, wave, lane, kt, K);
   }
   // k-tiles past the end of K come back as zeros (every lane out of range)
   __device__ __forceinline__ void issue(rsrc_t r, char* tile, int wave, int lane, int kt, int K) {
@@ -304,9 +322,8 @@ template <bool TA, bool TB> struct PanelTouch {
 // next tile's step 0, after the barrier) are issued before the MFMAs of step kk.  The barrier that
 // ends the reads of tile kt's stage sits before the last step's MFMAs, and the loads of tile kt+2
 // into that stage are issued right there (a whole k-tile ahead of their use) with the wave's
-// priority raised, so that the requests leave before the other wave's arithmetic.  With transposing reads
-// on the critical path (k-slow operands) the loads go out after the next tile's first fragment reads,
-// otherwise before them (measured: +9..14 % over issuing them at the top of the next iteration).
+// priority raised, so that the requests leave before the other wave's arithmetic; they go out after the
+// next tile's first fragment reads (measured: +9..14 % over issuing them at the top of the next iteration).
 // Measured on copies of this loop with parts removed (NT, all 256 CUs busy, per k-tile): MFMAs alone 1.28 us
 // (the chip's power limit on changing operands; 0.96 us on a lone CU), fragment reads +0.08, the barrier +0.12,
 // the loads +0.27 in the compiler's form (most of it the issue slots of their address arithmetic: see TileLoad);
@@ -527,20 +544,31 @@ __device__ __forceinline__ void gemm_mainloop16(f32x4_t (&acc)[kBM / WGM / 16][k
 #pragma unroll
   for (int j = 0; j < CB; ++j) bfr[0][j] = read_frag16<TB>(smem + kTileBytes, wn0 + j * 16, 0, lane);
 
-  auto request = [&](char* stage, int kt) {
+  // A stage is refilled in three instalments - operand A (and the touches) right behind the barrier that frees it,
+  // the two halves of operand B at the start of the next tile's phases 0 and 1 - so that a wave's eight loads do
+  // not queue up behind each other and the seven other waves' (measured against all eight at the barrier: data
+  // gradients +1.5..2.5 %, forward +1 %, -1.5 % at K = 3200; bit-equal).
+  auto request_a = [&](char* stage, int kt) {
     __builtin_amdgcn_s_setprio(1);
     la.issue(ra, stage, wave, lane, kt, kend);
-    lb.issue(rb, stage + kTileBytes, wave, lane, kt, kend);
     touch.issue(ra, rb, smem, wave, kt, kend);
     __builtin_amdgcn_s_setprio(0);
   };
-  request(smem + kStageBytes, kt0 + 1);
+  auto request_b = [&](char* stage, int kt, auto half) {
+    __builtin_amdgcn_s_setprio(1);
+    lb.template issue_half<decltype(half)::value>(rb, stage + kTileBytes, wave, lane, kt, kend);
+    __builtin_amdgcn_s_setprio(0);
+  };
+  request_a(smem + kStageBytes, kt0 + 1);
+  lb.issue(rb, smem + kStageBytes + kTileBytes, wave, lane, kt0 + 1, kend);
   for (int kt = kt0; kt < kt1; ++kt) {
     char* cur = smem + ((kt - kt0) & 1) * kStageBytes;
     char* nxt = smem + ((kt - kt0 + 1) & 1) * kStageBytes;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       const int ks = p >> 1, half = p & 1;
+      if (p == 0 && kt > kt0 && kt + 1 < kt1) request_b(nxt, kt + 1, std::integral_constant<int, 0>{});
+      if (p == 1 && kt > kt0 && kt + 1 < kt1) request_b(nxt, kt + 1, std::integral_constant<int, 1>{});
       if (p < 3) {
         const int q = p + 1, qs = q >> 1, qh = q & 1;
 #pragma unroll
@@ -560,7 +588,7 @@ __device__ __forceinline__ void gemm_mainloop16(f32x4_t (&acc)[kBM / WGM / 16][k
         // the refill goes out after the next tile's first fragment reads (ahead of them: data gradients 1-2 % slower,
         // the others the same); nothing is requested past the last tile: no load may be in flight when the epilogue
         // reuses LDS
-        if (kt + 2 < kt1) request(cur, kt + 2);
+        if (kt + 2 < kt1) request_a(cur, kt + 2);
       }
 #pragma unroll
       for (int i = 0; i < HB; ++i)
