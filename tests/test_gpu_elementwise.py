@@ -65,7 +65,7 @@ def test_layernorm_forward_backward(dtype, rows, width):
 
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("mode", [B.GELU_ERF, B.GELU_TANH])
-@pytest.mark.parametrize("rows,width", [(1, 8), (70, 264), (257, 1024), (33, 12800)])
+@pytest.mark.parametrize("rows,width", [(1, 8), (70, 264), (257, 1024), (33, 12800), (3, 1032), (35, 520)])
 def test_bias_gelu(dtype, mode, rows, width):
     z = randn((rows, width), dtype, 1, 2.0)
     bias = randn((width,), dtype, 2, 0.5)
@@ -89,7 +89,7 @@ def test_bias_gelu(dtype, mode, rows, width):
 
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("p", [0.0, 0.1, 0.5])
-@pytest.mark.parametrize("rows,width", [(1, 8), (70, 264), (256, 256), (19, 12288)])
+@pytest.mark.parametrize("rows,width", [(1, 8), (70, 264), (256, 256), (19, 12288), (3, 1032), (35, 520)])
 def test_bias_dropout_add(dtype, p, rows, width):
     seed, layer, site, mb = 42, 3, 1, 5
     a = randn((rows, width), dtype, 1)
