@@ -1,6 +1,6 @@
 """Each exported kernel alone at the shapes of a workload, against its roofline.
 
-    python -m paper_2104_04473_amd.kernel_bench [--shape c4|c3|c2] [--iters 10] [--only elementwise]
+    python -m paper_2104_04473_amd.kernel_bench [--shape c4|c3|c2] [--iters 10] [--only elementwise|attention]
 
 Element-wise kernels rotate over enough distinct buffers (> 512 MB in total) that the 256 MB memory-side
 cache cannot serve them; GEMMs and attention run on one buffer set (their operands exceed the caches or
@@ -21,7 +21,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--shape", default="c4", choices=sorted(SHAPES))
     ap.add_argument("--iters", type=int, default=10)
-    ap.add_argument("--only", default="all", choices=["all", "elementwise"])
+    ap.add_argument("--only", default="all", choices=["all", "elementwise", "attention"])
     args = ap.parse_args()
     import torch
     from . import binding as B
@@ -66,59 +66,62 @@ def main():
         per = T * width * 2 * n_tensors
         return max(2, -(-(600 << 20) // per))
 
-    # ---- element-wise kernels (bytes = algorithmic bytes of the bf16 path) ------------------------------
-    g = torch.ones(h, dtype=bf, device=dev); be = torch.zeros(h, dtype=bf, device=dev)
-    n = sets(h, 2)
-    xs = [rnd(T, h) for _ in range(n)]; us = [torch.empty(T, h, dtype=bf, device=dev) for _ in range(n)]
-    mu = torch.empty(T, device=dev); rstd = torch.empty(T, device=dev)
-    report("layernorm_fwd", T * h * 4, "GB/s",
-           [lambda i=i: B.ptdp_layernorm_fwd(B.BF16, xs[i].data_ptr(), g.data_ptr(), be.data_ptr(), us[i].data_ptr(),
-                                             mu.data_ptr(), rstd.data_ptr(), None, T, h, 1e-5, sh) for i in range(n)])
-    dg = torch.zeros(h, device=dev); db = torch.zeros(h, device=dev)
-    scratch = torch.empty(max(B.ptdp_layernorm_bwd_scratch_bytes(T, h), B.ptdp_colsum_scratch_bytes(T, max(h, fp))), dtype=torch.uint8, device=dev)
-    B.ptdp_layernorm_fwd(B.BF16, xs[0].data_ptr(), g.data_ptr(), be.data_ptr(), us[0].data_ptr(), mu.data_ptr(),
-                         rstd.data_ptr(), None, T, h, 1e-5, sh)
-    report("layernorm_bwd (dx + parameter gradients, with residual)", T * h * 12, "GB/s",
-           [lambda i=i: B.ptdp_layernorm_bwd(B.BF16, us[i].data_ptr(), xs[i].data_ptr(), g.data_ptr(), mu.data_ptr(),
-                                             rstd.data_ptr(), xs[(i + 1) % n].data_ptr(), us[i].data_ptr(), dg.data_ptr(),
-                                             db.data_ptr(), scratch.data_ptr(), T, h, sh) for i in range(n)])
-    report("bias_dropout_add_fwd", T * h * 6, "GB/s",
-           [lambda i=i: B.ptdp_bias_dropout_add_fwd(B.BF16, xs[i].data_ptr(), be.data_ptr(), xs[(i + 1) % n].data_ptr(),
-                                                    us[i].data_ptr(), T, h, 0.1, 0, 0, 0, 0, sh) for i in range(n)])
-    report("bias_dropout_add_bwd", T * h * 4, "GB/s",
-           [lambda i=i: B.ptdp_bias_dropout_add_bwd(B.BF16, xs[i].data_ptr(), us[i].data_ptr(), db.data_ptr(),
-                                                    scratch.data_ptr(), T, h, 0.1, 0, 0, 0, 0, sh) for i in range(n)])
-    del xs, us
-    n = sets(fp, 2)
-    zs = [rnd(T, fp) for _ in range(n)]; gs = [torch.empty(T, fp, dtype=bf, device=dev) for _ in range(n)]
-    b1 = torch.zeros(fp, dtype=bf, device=dev); db1 = torch.zeros(fp, device=dev)
-    report("bias_gelu_fwd", T * fp * 4, "GB/s",
-           [lambda i=i: B.ptdp_bias_gelu_fwd(B.BF16, B.GELU_ERF, zs[i].data_ptr(), b1.data_ptr(), gs[i].data_ptr(), T, fp, sh)
-            for i in range(n)])
-    report("bias_gelu_bwd", T * fp * 6, "GB/s",
-           [lambda i=i: B.ptdp_bias_gelu_bwd(B.BF16, B.GELU_ERF, gs[i].data_ptr(), zs[i].data_ptr(), b1.data_ptr(),
-                                             gs[i].data_ptr(), db1.data_ptr(), scratch.data_ptr(), T, fp, sh) for i in range(n)])
-    del zs, gs
+    if args.only in ("all", "elementwise"):
+        # ---- element-wise kernels (bytes = algorithmic bytes of the bf16 path) ------------------------------
+        g = torch.ones(h, dtype=bf, device=dev); be = torch.zeros(h, dtype=bf, device=dev)
+        n = sets(h, 2)
+        xs = [rnd(T, h) for _ in range(n)]; us = [torch.empty(T, h, dtype=bf, device=dev) for _ in range(n)]
+        mu = torch.empty(T, device=dev); rstd = torch.empty(T, device=dev)
+        report("layernorm_fwd", T * h * 4, "GB/s",
+               [lambda i=i: B.ptdp_layernorm_fwd(B.BF16, xs[i].data_ptr(), g.data_ptr(), be.data_ptr(), us[i].data_ptr(),
+                                                 mu.data_ptr(), rstd.data_ptr(), None, T, h, 1e-5, sh) for i in range(n)])
+        dg = torch.zeros(h, device=dev); db = torch.zeros(h, device=dev)
+        scratch = torch.empty(max(B.ptdp_layernorm_bwd_scratch_bytes(T, h), B.ptdp_colsum_scratch_bytes(T, max(h, fp))), dtype=torch.uint8, device=dev)
+        B.ptdp_layernorm_fwd(B.BF16, xs[0].data_ptr(), g.data_ptr(), be.data_ptr(), us[0].data_ptr(), mu.data_ptr(),
+                             rstd.data_ptr(), None, T, h, 1e-5, sh)
+        report("layernorm_bwd (dx + parameter gradients, with residual)", T * h * 12, "GB/s",
+               [lambda i=i: B.ptdp_layernorm_bwd(B.BF16, us[i].data_ptr(), xs[i].data_ptr(), g.data_ptr(), mu.data_ptr(),
+                                                 rstd.data_ptr(), xs[(i + 1) % n].data_ptr(), us[i].data_ptr(), dg.data_ptr(),
+                                                 db.data_ptr(), scratch.data_ptr(), T, h, sh) for i in range(n)])
+        report("bias_dropout_add_fwd", T * h * 6, "GB/s",
+               [lambda i=i: B.ptdp_bias_dropout_add_fwd(B.BF16, xs[i].data_ptr(), be.data_ptr(), xs[(i + 1) % n].data_ptr(),
+                                                        us[i].data_ptr(), T, h, 0.1, 0, 0, 0, 0, sh) for i in range(n)])
+        report("bias_dropout_add_bwd", T * h * 4, "GB/s",
+               [lambda i=i: B.ptdp_bias_dropout_add_bwd(B.BF16, xs[i].data_ptr(), us[i].data_ptr(), db.data_ptr(),
+                                                        scratch.data_ptr(), T, h, 0.1, 0, 0, 0, 0, sh) for i in range(n)])
+        del xs, us
+        n = sets(fp, 2)
+        zs = [rnd(T, fp) for _ in range(n)]; gs = [torch.empty(T, fp, dtype=bf, device=dev) for _ in range(n)]
+        b1 = torch.zeros(fp, dtype=bf, device=dev); db1 = torch.zeros(fp, device=dev)
+        report("bias_gelu_fwd", T * fp * 4, "GB/s",
+               [lambda i=i: B.ptdp_bias_gelu_fwd(B.BF16, B.GELU_ERF, zs[i].data_ptr(), b1.data_ptr(), gs[i].data_ptr(), T, fp, sh)
+                for i in range(n)])
+        report("bias_gelu_bwd", T * fp * 6, "GB/s",
+               [lambda i=i: B.ptdp_bias_gelu_bwd(B.BF16, B.GELU_ERF, gs[i].data_ptr(), zs[i].data_ptr(), b1.data_ptr(),
+                                                 gs[i].data_ptr(), db1.data_ptr(), scratch.data_ptr(), T, fp, sh) for i in range(n)])
+        del zs, gs
+
+    if args.only == "all":
+        # ---- GEMMs of one layer ----------------------------------------------------------------------------
+        ws = torch.empty(B.ptdp_gemm_workspace_bytes(), dtype=torch.uint8, device=dev)
+        fwd = [("qkv", 3 * hp, h), ("attention output", h, hp), ("mlp h->4h/t", fp, h), ("mlp 4h/t->h", h, fp)]
+        for name, N, K in fwd:
+            a = rnd(T, K); wgt = rnd(K, N, scale=0.02); c = torch.empty(T, N, dtype=bf, device=dev)
+            report("gemm forward %s [%d x %d x %d]" % (name, T, N, K), 2.0 * T * N * K, "TFLOP/s",
+                   [lambda: B.ptdp_gemm(B.BF16, B.GEMM_NN, a.data_ptr(), wgt.data_ptr(), c.data_ptr(), None, T, N, K, 0, 0,
+                                        ws.data_ptr(), ws.numel(), sh)])
+            dy = rnd(T, N); dx = torch.empty(T, K, dtype=bf, device=dev)
+            report("gemm data gradient %s [%d x %d x %d]" % (name, T, K, N), 2.0 * T * N * K, "TFLOP/s",
+                   [lambda: B.ptdp_gemm(B.BF16, B.GEMM_NT, dy.data_ptr(), wgt.data_ptr(), dx.data_ptr(), None, T, K, N, 0, 0,
+                                        ws.data_ptr(), ws.numel(), sh)])
+            dw = torch.zeros(K, N, device=dev)
+            report("gemm weight gradient %s [%d x %d x %d]" % (name, K, N, T), 2.0 * T * N * K, "TFLOP/s",
+                   [lambda: B.ptdp_gemm(B.BF16, B.GEMM_TN, a.data_ptr(), dy.data_ptr(), dw.data_ptr(), None, K, N, T, 1, 1,
+                                        ws.data_ptr(), ws.numel(), sh)])
+            del a, wgt, c, dy, dx, dw
+
     if args.only == "elementwise":
         return
-
-    # ---- GEMMs of one layer ----------------------------------------------------------------------------
-    ws = torch.empty(B.ptdp_gemm_workspace_bytes(), dtype=torch.uint8, device=dev)
-    fwd = [("qkv", 3 * hp, h), ("attention output", h, hp), ("mlp h->4h/t", fp, h), ("mlp 4h/t->h", h, fp)]
-    for name, N, K in fwd:
-        a = rnd(T, K); wgt = rnd(K, N, scale=0.02); c = torch.empty(T, N, dtype=bf, device=dev)
-        report("gemm forward %s [%d x %d x %d]" % (name, T, N, K), 2.0 * T * N * K, "TFLOP/s",
-               [lambda: B.ptdp_gemm(B.BF16, B.GEMM_NN, a.data_ptr(), wgt.data_ptr(), c.data_ptr(), None, T, N, K, 0, 0,
-                                    ws.data_ptr(), ws.numel(), sh)])
-        dy = rnd(T, N); dx = torch.empty(T, K, dtype=bf, device=dev)
-        report("gemm data gradient %s [%d x %d x %d]" % (name, T, K, N), 2.0 * T * N * K, "TFLOP/s",
-               [lambda: B.ptdp_gemm(B.BF16, B.GEMM_NT, dy.data_ptr(), wgt.data_ptr(), dx.data_ptr(), None, T, K, N, 0, 0,
-                                    ws.data_ptr(), ws.numel(), sh)])
-        dw = torch.zeros(K, N, device=dev)
-        report("gemm weight gradient %s [%d x %d x %d]" % (name, K, N, T), 2.0 * T * N * K, "TFLOP/s",
-               [lambda: B.ptdp_gemm(B.BF16, B.GEMM_TN, a.data_ptr(), dy.data_ptr(), dw.data_ptr(), None, K, N, T, 1, 1,
-                                    ws.data_ptr(), ws.numel(), sh)])
-        del a, wgt, c, dy, dx, dw
 
     # ---- attention -------------------------------------------------------------------------------------
     qkv = rnd(w["s"], w["b"], 3 * hp); ctx = torch.empty(w["s"], w["b"], hp, dtype=bf, device=dev)
